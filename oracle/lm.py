@@ -1,0 +1,202 @@
+"""Decoder-only transformer language model: next-token cross-entropy loss and its gradient.
+
+The paper fixes only "decoder-only transformer" (appendix, Network Architecture / model
+configuration table) and "cross entropy loss for next token prediction" (Background, Eq. 1).
+The reading used here: pre-norm blocks with RMSNorm (eps 1e-5, learned gain), causal
+multi-head softmax attention with scale 1/sqrt(dh), tanh-GELU feed-forward, learned
+absolute position embeddings, no biases, no dropout, untied input/output embeddings, loss
+averaged over all B*S predicted positions.
+
+Flat parameter vector layout (all row-major):
+  E [V,d], Ppos [S,d], then per layer Wqkv [d,3d] (columns q|k|v, head-major inside each),
+  Wo [d,d], W1 [d,ff], W2 [ff,d]; then Wout [d,V]; then all gains: per layer g1 [d], g2 [d];
+  finally gf [d].  Everything before the gains is weight-decayed, the gains are not.
+"""
+from __future__ import annotations
+
+import math
+import numpy as np
+
+
+def param_layout(cfg):
+    """List of (name, shape, kind); kind is "matrix" (decayed) or "gain" (not decayed)."""
+    L, d, ff, V, S = cfg["L"], cfg["d"], cfg["ff"], cfg["V"], cfg["S"]
+    out = [("E", (V, d), "matrix"), ("Ppos", (S, d), "matrix")]
+    for l in range(L):
+        out += [(f"Wqkv{l}", (d, 3 * d), "matrix"), (f"Wo{l}", (d, d), "matrix"),
+                (f"W1{l}", (d, ff), "matrix"), (f"W2{l}", (ff, d), "matrix")]
+    out.append(("Wout", (d, V), "matrix"))
+    for l in range(L):
+        out += [(f"g1{l}", (d,), "gain"), (f"g2{l}", (d,), "gain")]
+    out.append(("gf", (d,), "gain"))
+    return out
+
+
+def n_params(cfg):
+    return sum(int(np.prod(s)) for _, s, _ in param_layout(cfg))
+
+
+def n_decayed(cfg):
+    return sum(int(np.prod(s)) for _, s, k in param_layout(cfg) if k == "matrix")
+
+
+def views(flat, cfg):
+    """Dict name -> reshaped view into the flat vector."""
+    out, off = {}, 0
+    for name, shape, _ in param_layout(cfg):
+        n = int(np.prod(shape))
+        out[name] = flat[off:off + n].reshape(shape)
+        off += n
+    assert off == flat.size
+    return out
+
+
+# ---------------------------------------------------------------------------------------
+# pieces
+# ---------------------------------------------------------------------------------------
+def rmsnorm_fwd(x, g, eps):
+    rstd = 1.0 / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + x.dtype.type(eps))
+    return x * rstd * g, rstd
+
+
+def rmsnorm_bwd(dy, x, rstd, g):
+    xhat = x * rstd
+    dg = np.sum((dy * xhat).reshape(-1, x.shape[-1]), axis=0)
+    dxhat = dy * g
+    dx = rstd * (dxhat - xhat * np.mean(dxhat * xhat, axis=-1, keepdims=True))
+    return dx, dg
+
+
+_GELU_A = math.sqrt(2.0 / math.pi)
+_GELU_B = 0.044715
+
+
+def gelu_fwd(u):
+    t = u.dtype.type
+    return t(0.5) * u * (t(1.0) + np.tanh(t(_GELU_A) * (u + t(_GELU_B) * u * u * u)))
+
+
+def gelu_grad(u):
+    t = u.dtype.type
+    th = np.tanh(t(_GELU_A) * (u + t(_GELU_B) * u * u * u))
+    inner = t(_GELU_A) * (t(1.0) + t(3.0 * _GELU_B) * u * u)
+    return t(0.5) * (t(1.0) + th) + t(0.5) * u * (t(1.0) - th * th) * inner
+
+
+def attention_fwd(q, k, v):
+    """q,k,v [B,h,S,dh] -> o [B,h,S,dh], p [B,h,S,S] (causal softmax probabilities)."""
+    S, dh = q.shape[2], q.shape[3]
+    s = np.matmul(q, np.swapaxes(k, -1, -2)) * q.dtype.type(1.0 / math.sqrt(dh))
+    mask = np.triu(np.ones((S, S), dtype=bool), k=1)
+    s = np.where(mask, -np.inf, s)
+    s = s - np.max(s, axis=-1, keepdims=True)
+    p = np.exp(s)
+    p = p / np.sum(p, axis=-1, keepdims=True)
+    return np.matmul(p, v), p
+
+
+def attention_bwd(do, q, k, v, p):
+    dh = q.shape[3]
+    dv = np.matmul(np.swapaxes(p, -1, -2), do)
+    dp = np.matmul(do, np.swapaxes(v, -1, -2))
+    ds = p * (dp - np.sum(dp * p, axis=-1, keepdims=True))
+    ds = ds * q.dtype.type(1.0 / math.sqrt(dh))
+    dq = np.matmul(ds, k)
+    dk = np.matmul(np.swapaxes(ds, -1, -2), q)
+    return dq, dk, dv
+
+
+def _split_heads(x, B, S, h):
+    return x.reshape(B, S, h, -1).transpose(0, 2, 1, 3)
+
+
+def _merge_heads(x):
+    B, h, S, dh = x.shape
+    return x.transpose(0, 2, 1, 3).reshape(B * S, h * dh)
+
+
+# ---------------------------------------------------------------------------------------
+# loss and gradient
+# ---------------------------------------------------------------------------------------
+def forward(theta, tokens, cfg, keep=True):
+    """tokens int [B,S+1].  Returns (loss, cache).  Also cache["logits"] [B*S,V]."""
+    p = views(theta, cfg)
+    L, d, h, S = cfg["L"], cfg["d"], cfg["h"], cfg["S"]
+    eps = cfg["norm_eps"]
+    B = tokens.shape[0]
+    assert tokens.shape[1] == S + 1
+    inp, tgt = tokens[:, :S], tokens[:, 1:].reshape(-1)
+    x = (p["E"][inp] + p["Ppos"][None, :, :]).reshape(B * S, d)
+    layers = []
+    for l in range(L):
+        a, rstd1 = rmsnorm_fwd(x, p[f"g1{l}"], eps)
+        qkv = a @ p[f"Wqkv{l}"]
+        q = _split_heads(qkv[:, :d], B, S, h)
+        k = _split_heads(qkv[:, d:2 * d], B, S, h)
+        v = _split_heads(qkv[:, 2 * d:], B, S, h)
+        o4, prob = attention_fwd(q, k, v)
+        o = _merge_heads(o4)
+        xm = x + o @ p[f"Wo{l}"]
+        b, rstd2 = rmsnorm_fwd(xm, p[f"g2{l}"], eps)
+        u = b @ p[f"W1{l}"]
+        gl = gelu_fwd(u)
+        xn = xm + gl @ p[f"W2{l}"]
+        if keep:
+            layers.append(dict(x=x, a=a, rstd1=rstd1, q=q, k=k, v=v, prob=prob, o=o, xm=xm,
+                               b=b, rstd2=rstd2, u=u, gl=gl))
+        x = xn
+    xf, rstdf = rmsnorm_fwd(x, p["gf"], eps)
+    logits = xf @ p["Wout"]
+    mx = np.max(logits, axis=-1, keepdims=True)
+    lse = mx[:, 0] + np.log(np.sum(np.exp(logits - mx), axis=-1))
+    T = B * S
+    loss = np.mean(lse - logits[np.arange(T), tgt])
+    cache = dict(inp=inp, tgt=tgt, layers=layers, x=x, xf=xf, rstdf=rstdf, logits=logits,
+                 lse=lse, B=B)
+    return loss, cache
+
+
+def backward(theta, cache, cfg):
+    """Flat gradient of the mean loss, same layout as theta."""
+    p = views(theta, cfg)
+    grad = np.zeros_like(theta)
+    g = views(grad, cfg)
+    L, d, h, S = cfg["L"], cfg["d"], cfg["h"], cfg["S"]
+    B = cache["B"]
+    T = B * S
+    logits, lse, tgt = cache["logits"], cache["lse"], cache["tgt"]
+    dlogits = np.exp(logits - lse[:, None])
+    dlogits[np.arange(T), tgt] -= 1.0
+    dlogits = dlogits * theta.dtype.type(1.0 / T)
+    g["Wout"][...] = cache["xf"].T @ dlogits
+    dxf = dlogits @ p["Wout"].T
+    dx, dgf = rmsnorm_bwd(dxf, cache["x"], cache["rstdf"], p["gf"])
+    g["gf"][...] = dgf
+    for l in reversed(range(L)):
+        c = cache["layers"][l]
+        g[f"W2{l}"][...] = c["gl"].T @ dx
+        dgl = dx @ p[f"W2{l}"].T
+        du = dgl * gelu_grad(c["u"])
+        g[f"W1{l}"][...] = c["b"].T @ du
+        db = du @ p[f"W1{l}"].T
+        dxm_n, dg2 = rmsnorm_bwd(db, c["xm"], c["rstd2"], p[f"g2{l}"])
+        g[f"g2{l}"][...] = dg2
+        dxm = dx + dxm_n
+        g[f"Wo{l}"][...] = c["o"].T @ dxm
+        do = _split_heads(dxm @ p[f"Wo{l}"].T, B, S, h)
+        dq, dk, dv = attention_bwd(do, c["q"], c["k"], c["v"], c["prob"])
+        dqkv = np.concatenate([_merge_heads(dq), _merge_heads(dk), _merge_heads(dv)], axis=1)
+        g[f"Wqkv{l}"][...] = c["a"].T @ dqkv
+        da = dqkv @ p[f"Wqkv{l}"].T
+        dx_n, dg1 = rmsnorm_bwd(da, c["x"], c["rstd1"], p[f"g1{l}"])
+        g[f"g1{l}"][...] = dg1
+        dx = dxm + dx_n
+    dx3 = dx.reshape(B, S, d)
+    g["Ppos"][...] = dx3.sum(axis=0)
+    np.add.at(g["E"], cache["inp"].reshape(-1), dx)
+    return grad
+
+
+def loss_and_grad(theta, tokens, cfg):
+    loss, cache = forward(theta, tokens, cfg)
+    return loss, backward(theta, cache, cfg)

@@ -1,0 +1,85 @@
+"""Whole runs: asynchronous Local-SGD with Delayed Nesterov + DyLU (Alg. 2 + Alg. 3 +
+Eq. DyLU, workers running the inner loop of Alg. 1), and an independently written
+synchronous DiLoCo loop (Alg. 1) used to pin the synchronous special case.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import lm
+from .optim import AdamW, DelayedNesterov, dylu_steps, nesterov_step, pseudo_gradient
+from .scheduler import event_trace
+
+
+class Worker:
+    def __init__(self, idx, theta, cfg, stream, dtype):
+        self.idx = idx
+        self.theta = theta.copy()
+        self.theta_start = theta.copy()
+        self.opt = AdamW(theta.size, dtype, cfg["beta1"], cfg["beta2"], cfg["adam_eps"], cfg["wd"],
+                         lm.n_decayed(cfg))
+        self.stream = stream
+        self.losses = []
+
+    def restart(self, theta):
+        self.theta = theta.copy()
+        self.theta_start = theta.copy()
+
+    def local_steps(self, n, cfg, lrs=None):
+        """Inner loop of Alg. 1: n times (batch, loss, gradient, AdamW)."""
+        toks = self.stream.take(n)
+        for s in range(n):
+            loss, grad = lm.loss_and_grad(self.theta, toks[s], cfg)
+            self.opt.step(self.theta, grad, cfg["lr"] if lrs is None else lrs[s])
+            self.losses.append(float(loss))
+
+
+def run_async(cfg, theta0, make_stream, dtype=np.float32, n_events=None, log=None):
+    """Returns dict(theta, m, delta, t, losses[k][...], steps, groups, workers)."""
+    theta0 = theta0.astype(dtype)
+    k = cfg["k"]
+    steps = dylu_steps(cfg["speeds"], cfg["H"])
+    n_events = cfg["n_events"] if n_events is None else n_events
+    groups = event_trace(cfg["speeds"], steps, cfg["tau_grace"], n_events)
+    server = DelayedNesterov(theta0, cfg["outer_lr"], cfg["outer_beta"], cfg["N"], cfg["dn_c"])
+    workers = [Worker(i, theta0, cfg, make_stream(i), dtype) for i in range(k)]
+    for w in workers:                       # train(W, theta) before the loop
+        w.local_steps(int(steps[w.idx]), cfg)
+    for g in groups:
+        for (wi, _t) in g["events"]:
+            w = workers[wi]
+            server.event(pseudo_gradient(w.theta_start, w.theta))
+            if log is not None:
+                log(server, wi)
+        if g["complete"]:                   # train(W_completed, theta)
+            for (wi, _t) in g["events"]:
+                workers[wi].restart(server.theta)
+            if g is not groups[-1]:
+                for (wi, _t) in g["events"]:
+                    workers[wi].local_steps(int(steps[wi]), cfg)
+    return dict(theta=server.theta, m=server.m, delta=server.delta, t=server.t,
+                losses=[w.losses for w in workers], steps=steps, groups=groups, workers=workers)
+
+
+def run_diloco_sync(cfg, theta0, make_stream, n_outer, H, dtype=np.float32):
+    """Alg. 1 with AdamW inside and Nesterov (Eq. nesterov) outside, written on its own."""
+    theta = theta0.astype(dtype).copy()
+    m = np.zeros_like(theta)
+    k = cfg["k"]
+    opts = [AdamW(theta.size, dtype, cfg["beta1"], cfg["beta2"], cfg["adam_eps"], cfg["wd"],
+                  lm.n_decayed(cfg)) for _ in range(k)]
+    streams = [make_stream(i) for i in range(k)]
+    losses = [[] for _ in range(k)]
+    for _ in range(n_outer):
+        deltas = []
+        for i in range(k):
+            th = theta.copy()
+            toks = streams[i].take(H)
+            for s in range(H):
+                loss, grad = lm.loss_and_grad(th, toks[s], cfg)
+                opts[i].step(th, grad, cfg["lr"])
+                losses[i].append(float(loss))
+            deltas.append(theta - th)
+        mean_delta = sum(deltas) / dtype(k)
+        theta, m = nesterov_step(theta, m, mean_delta, cfg["outer_lr"], cfg["outer_beta"])
+    return dict(theta=theta, m=m, losses=losses)
