@@ -1,0 +1,188 @@
+/*
+ * als.h -- C ABI of the asynchronous Local-SGD hot path for AMD MI355X (gfx950).
+ *
+ * What the library computes (citations are to arXiv 2401.09135, "Asynchronous Local-SGD
+ * Training for Language Modeling"):
+ *   - a worker's local round: the inner loop of Alg. 1 (sample a batch, next-token
+ *     cross-entropy loss of a decoder-only transformer, gradient, AdamW update), with the
+ *     AdamW state kept on the worker across rounds (appendix, "Inner Optimizer States");
+ *   - the server's sync() step of Alg. 2: pseudo-gradient (Alg. 1, delta = theta_start -
+ *     theta_worker) fed to the Delayed Nesterov update of Alg. 3, then the restart of the
+ *     synchronised workers from the new global parameters (Alg. 2, train(W_completed));
+ *   - Dynamic Local Updates (Eq. DyLU) and the deterministic event order of Alg. 2 with
+ *     get_worker() from the appendix on a simulated clock.
+ *
+ * Conventions
+ *   - Every function returns an int status: 0 = ALS_OK, negative = error.  Nothing throws
+ *     and nothing aborts; als_last_error() returns the text of the calling thread's last
+ *     error.
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are host addresses.
+ *   - The library never allocates device memory except in the als_k_* test entry points'
+ *     callers' own buffers: als_init() carves everything out of one caller-owned arena.
+ *     Streams are borrowed hipStream_t handles passed as void*.
+ *   - Flat parameter vector layout (row-major tensors, fp32), P elements in total:
+ *       E [V,d], Ppos [S,d], per layer: Wqkv [d,3d] (columns q|k|v, head-major inside each),
+ *       Wo [d,d], W1 [d,ff], W2 [ff,d]; Wout [d,V]; then the RMSNorm gains: per layer g1 [d],
+ *       g2 [d]; finally gf [d].  The first P_decay elements (everything but the gains) are
+ *       weight-decayed.
+ *   - Model (reading of "decoder-only transformer", appendix "Network Architecture"):
+ *     pre-norm blocks, RMSNorm, causal softmax attention scaled by 1/sqrt(d/h), tanh-GELU FFN,
+ *     learned positions, no bias, untied output matrix, loss averaged over B*S positions.
+ */
+#ifndef ALS_H
+#define ALS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ALS_OK 0
+#define ALS_ERR_INVALID (-1) /* bad argument or configuration */
+#define ALS_ERR_ARENA (-2)   /* arena too small or misaligned */
+#define ALS_ERR_HIP (-3)     /* a HIP runtime call failed */
+#define ALS_ERR_STATE (-4)   /* call not valid in the context's current state */
+
+#define ALS_DTYPE_F32 0  /* fp32 everywhere (debug / reference mode) */
+#define ALS_DTYPE_BF16 1 /* bf16 GEMM and attention operands, fp32 accumulate, master, optimiser */
+
+#define ALS_MAX_WORKERS 64
+
+/* Plain-data configuration.  Notation follows the paper: k workers, N = Delayed Nesterov
+ * buffer size, c = momentum activation, eps_outer/beta = outer learning rate and decay. */
+typedef struct als_config {
+  int32_t n_layers;        /* L */
+  int32_t d_model;         /* d, multiple of 64 */
+  int32_t n_heads;         /* h, d/h in {32, 64} */
+  int32_t d_ff;            /* ff, multiple of 64 */
+  int32_t vocab;           /* V */
+  int32_t seq_len;         /* S (tokens carry S+1 per sample), <= 1024 */
+  int32_t batch;           /* B samples per worker step */
+  int32_t dtype;           /* ALS_DTYPE_* */
+  int32_t n_workers;       /* k, 1..ALS_MAX_WORKERS */
+  int32_t dn_N;            /* N >= 1 */
+  int32_t max_local_steps; /* capacity of the per-worker loss buffer (>= largest n_steps) */
+  int32_t flags;           /* bit 0: disable the MFMA kernels (use the generic ones) */
+  double adam_beta1, adam_beta2, adam_eps, weight_decay; /* AdamW (inner optimiser) */
+  double outer_lr, outer_beta, dn_c;                     /* Alg. 3: epsilon, beta, c in [0,1/N] */
+  double norm_eps;                                       /* RMSNorm epsilon */
+} als_config;
+
+typedef struct als_ctx als_ctx;
+
+const char* als_last_error(void);
+
+/* Number of parameters P / decayed parameters for a configuration (0 if invalid). */
+int64_t als_param_count(const als_config* cfg);
+int64_t als_param_count_decayed(const als_config* cfg);
+/* Offsets (in elements) of the tensors of the flat layout, in layout order:
+ * E, Ppos, L x (Wqkv, Wo, W1, W2), Wout, L x (g1, g2), gf  ->  4L + 2L + 4 entries.
+ * offsets_out has room for n_out int64; returns the number of tensors or a negative error. */
+int als_param_offsets(const als_config* cfg, int64_t* offsets_out, int n_out);
+
+/* Device bytes als_init() needs for this configuration (0 if invalid). */
+size_t als_arena_bytes(const als_config* cfg);
+
+/* Alg. 2 lines 1-3: theta <- theta0, create the k workers.  Copies theta0_host (P floats,
+ * host) into the server parameters and into every worker replica (master, round-start
+ * snapshot and, in bf16 mode, the bf16 working copy); zeroes the outer momentum m, the
+ * buffer Delta, the event counter t and every worker's AdamW state.
+ *   arena_dev/arena_bytes: caller-owned device memory, 256-byte aligned, >= als_arena_bytes;
+ *     must outlive the context.  streams: n_streams >= 1 borrowed hipStream_t; worker w runs
+ *     on streams[w % n_streams].  *out is owned by the library until als_destroy(). */
+int als_init(const als_config* cfg, void* arena_dev, size_t arena_bytes, const float* theta0_host,
+             void* const* streams, int n_streams, als_ctx** out);
+int als_destroy(als_ctx* ctx);
+
+/* Alg. 1 inner loop for one worker, from its current replica: n_steps times (loss on the
+ * next batch, backward, AdamW with this step's learning rate).  AdamW moments and step
+ * count persist across calls and restarts.
+ *   tokens_dev: int32 [n_steps, B, S+1] on the device, values in [0, V) (ids outside the range
+ *     are clamped into it, never dereferenced); position s predicts s+1.  lr_host: n_steps floats (host), read before the call returns.
+ *   loss_host_or_null: if non-null receives the n_steps mean losses and the call waits for
+ *     the worker's stream; if null the call only enqueues work (fetch the losses later with
+ *     als_get_losses after als_sync).  Does not touch server state. */
+int als_worker_local_steps(als_ctx* ctx, int worker, int n_steps, const int32_t* tokens_dev,
+                           const float* lr_host, float* loss_host_or_null);
+
+/* sync() of Alg. 2 for a group of workers that completed together, in the given order.
+ * For each: g = theta_start - theta_worker (pseudo-gradient), one event of Alg. 3
+ * (Delta += g; every N-th event m <- beta m + Delta/N, theta <- theta - eps((1-cN+c) beta m
+ * + g/N), Delta <- 0; otherwise theta <- theta - eps(c beta m + g/N)), t <- t+1.  If
+ * restart_flag != 0 every listed worker then restarts from the new theta (replica, snapshot,
+ * bf16 copy); its AdamW state is kept.  A group call equals n_group single calls followed by
+ * the restarts.  Ordered after the listed workers' pending local steps. */
+int als_outer_apply_dn(als_ctx* ctx, const int32_t* workers, int n_group, int restart_flag);
+
+/* Eq. (DyLU) and, optionally, the event order of Alg. 2 on the simulated clock.  Host only.
+ *   H_out[k] = max(1, floor(speeds[i] / max(speeds) * H_max)) in fp64.
+ *   If ev_worker is non-null, also writes the first n_events sync events: worker index,
+ *   completion time (job length = H_i / speeds[i]; all start at 0; restarts at tau_sync +
+ *   tau_grace) and a flag that is 1 on the last event of a group whose workers then restart
+ *   (ties and arrivals within tau_grace of the group's first event share a group; ties are
+ *   ordered by worker index).  ev_time and ev_group_end may be null.
+ *   Errors: k <= 0 or > ALS_MAX_WORKERS, non-finite or non-positive speed, H_max < 1,
+ *   tau_grace < 0 or non-finite, n_events < 0. */
+int als_dylu_schedule(const double* speeds, int k, int H_max, double tau_grace, int n_events,
+                      int32_t* H_out, int32_t* ev_worker, double* ev_time, int32_t* ev_group_end);
+
+/* ---- helpers for tests and drivers -------------------------------------------------- */
+#define ALS_VEC_THETA 0        /* server parameters              (worker ignored) */
+#define ALS_VEC_MOMENTUM 1     /* server momentum m              (worker ignored) */
+#define ALS_VEC_DELTA 2        /* server buffer Delta            (worker ignored) */
+#define ALS_VEC_WORKER_THETA 3 /* worker replica (fp32 master)   */
+#define ALS_VEC_WORKER_START 4 /* worker round-start snapshot    */
+#define ALS_VEC_ADAM_M 5
+#define ALS_VEC_ADAM_V 6
+#define ALS_VEC_GRAD 7         /* worker's last gradient         */
+/* Copy a length-P fp32 vector to / from the host; waits for all pending work first. */
+int als_get_vector(als_ctx* ctx, int which, int worker, float* host_out);
+int als_set_vector(als_ctx* ctx, int which, int worker, const float* host_in);
+/* Wait for one worker's stream (worker >= 0) or for everything (worker < 0). */
+int als_sync(als_ctx* ctx, int worker);
+/* Losses of the worker's most recent als_worker_local_steps call (n <= its n_steps). */
+int als_get_losses(als_ctx* ctx, int worker, float* host_out, int n);
+/* Number of Alg. 3 events applied so far (t). */
+int64_t als_server_t(als_ctx* ctx);
+/* AdamW step count of a worker. */
+int64_t als_worker_adam_steps(als_ctx* ctx, int worker);
+/* Loss and gradient of one batch at the worker's current replica, no update (for parity
+ * tests): tokens_dev int32 [B,S+1]; loss_host 1 float; the gradient is left in
+ * ALS_VEC_GRAD.  Synchronous. */
+int als_worker_loss_grad(als_ctx* ctx, int worker, const int32_t* tokens_dev, float* loss_host);
+
+/* ---- stand-alone kernels on caller-owned device vectors (microbenchmarks, unit tests) -- */
+/* One pass of Alg. 3 over G pseudo-gradients g_j = theta_start[j] - theta_worker[j] applied
+ * in order to (theta, m, delta), all fp32 device vectors of length P; t0 = number of events
+ * applied before the call.  If restart != 0, afterwards writes the new theta into every
+ * theta_worker[j], theta_start[j] and (if bf16_worker[j] non-null) a bf16 copy.  G <= 16.
+ * Pointer arrays are host arrays of device pointers. */
+int als_k_dn_group(float* theta, float* m, float* delta, float* const* theta_start,
+                   float* const* theta_worker, void* const* bf16_worker, int G, int64_t P, int N,
+                   int64_t t0, double outer_lr, double beta, double c, int restart, void* stream);
+/* One fused AdamW step over flat fp32 device vectors of length P (first P_decay decayed);
+ * step = 1-based count used for bias correction; bf16_out may be null. */
+int als_k_adamw(float* theta, const float* grad, float* m, float* v, void* bf16_out, int64_t P,
+                int64_t P_decay, int64_t step, double lr, double beta1, double beta2, double eps,
+                double wd, void* stream);
+/* C = A.B with fp32 accumulation.  a_layout 0: A is [M,K] row-major, 1: A is stored [K,M];
+ * b_layout 0: B is [K,N] row-major, 1: B is stored [N,K].  in_dtype/out_dtype ALS_DTYPE_*;
+ * use_mfma != 0 selects the MFMA kernel (bf16 inputs, M,N multiples of 128, K of 64).
+ * ws_dev/ws_bytes: optional device scratch for split-K partials (may be null / 0). */
+int als_k_gemm(const void* A, const void* B, void* C, int M, int N, int K, int a_layout,
+               int b_layout, int in_dtype, int out_dtype, int use_mfma, void* ws_dev,
+               size_t ws_bytes, void* stream);
+/* Causal attention forward / backward on packed qkv [B*S, 3d] (q|k|v, head-major), dtype
+ * ALS_DTYPE_*: o [B*S,d] same dtype, lse fp32 [B,h,S]; backward takes d_o and returns dqkv. */
+int als_k_attention_fwd(const void* qkv, void* o, float* lse, int B, int S, int h, int dh,
+                        int dtype, int use_mfma, void* stream);
+int als_k_attention_bwd(const void* qkv, const void* o, const void* d_o, const float* lse,
+                        float* dscratch, void* dqkv, int B, int S, int h, int dh, int dtype,
+                        int use_mfma, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ALS_H */

@@ -1,0 +1,14 @@
+"""Asynchronous Local-SGD hot path on MI355X: thin Python binding over libals.so.
+
+The binding only marshals arguments (ctypes) and uses torch for device memory and streams;
+every step of the path runs inside the library's HIP kernels.  Importing this package fails
+loudly if the library has not been built (``python -m paper_2401_09135_amd.build``).
+"""
+from .binding import (ALS_DTYPE_BF16, ALS_DTYPE_F32, AlsError, Config, Context, VEC, dylu_schedule,
+                      k_adamw, k_attention_bwd, k_attention_fwd, k_dn_group, k_gemm, lib, lib_path,
+                      param_count, param_count_decayed, param_offsets)
+from .driver import run_async
+
+__all__ = ["ALS_DTYPE_BF16", "ALS_DTYPE_F32", "AlsError", "Config", "Context", "VEC",
+           "dylu_schedule", "k_adamw", "k_attention_bwd", "k_attention_fwd", "k_dn_group", "k_gemm",
+           "lib", "lib_path", "param_count", "param_count_decayed", "param_offsets", "run_async"]

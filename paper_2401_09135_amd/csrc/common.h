@@ -1,0 +1,121 @@
+// Internal declarations shared by the library's translation units (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/als.h"
+
+namespace als {
+
+typedef __bf16 bf16;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+int set_error(int code, const char* fmt, ...);
+
+#define ALS_HIP(expr)                                                                      \
+  do {                                                                                     \
+    hipError_t e_ = (expr);                                                                \
+    if (e_ != hipSuccess)                                                                  \
+      return als::set_error(ALS_ERR_HIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), \
+                            __FILE__, __LINE__);                                           \
+  } while (0)
+
+#define ALS_CHECK_LAUNCH() ALS_HIP(hipGetLastError())
+
+// ---- parameter layout -----------------------------------------------------------------
+struct Layout {
+  int64_t E, Ppos, Wout, gf;
+  int64_t Wqkv[64], Wo[64], W1[64], W2[64], g1[64], g2[64];
+  int64_t P, P_decay;
+};
+int validate_config(const als_config* c);
+void make_layout(const als_config& c, Layout* L);
+
+// ---- GEMM -------------------------------------------------------------------------------
+enum Epilogue {
+  EPI_STORE = 0,   // C = acc
+  EPI_RESID = 1,   // C(fp32) = R(fp32) + acc
+  EPI_GELU = 2,    // C = acc (pre-activation), C2 = gelu_tanh(acc)
+  EPI_DGELU = 3,   // C = acc * gelu_tanh'(U)
+};
+
+struct GemmDesc {
+  const void* A; const void* B;
+  int M, N, K;
+  int a_layout;  // 0: A[m*lda + k] ; 1: A[k*lda + m]
+  int b_layout;  // 0: B[k*ldb + n] ; 1: B[n*ldb + k]
+  int64_t lda, ldb;
+  int in_bf16;   // operands bf16 (else fp32)
+  void* C; int64_t ldc; int c_bf16;  // output type
+  int epi;
+  const float* R; int64_t ldr;       // EPI_RESID
+  void* C2;                          // EPI_GELU second output (same type/ld as C)
+  const void* U;                     // EPI_DGELU pre-activation (operand type, ld = ldc)
+  float* ws; size_t ws_bytes;        // scratch for split-K partials (may be null)
+};
+int gemm_generic(const GemmDesc& g, hipStream_t st);
+bool gemm_mfma_supported(const GemmDesc& g);
+int gemm_mfma(const GemmDesc& g, hipStream_t st);
+// picks the MFMA kernel when allowed and supported
+int gemm(const GemmDesc& g, bool allow_mfma, hipStream_t st);
+
+// ---- attention ----------------------------------------------------------------------------
+int attention_fwd_generic(const void* qkv, void* o, float* lse, int B, int S, int h, int dh,
+                          int bf, hipStream_t st);
+int attention_bwd_generic(const void* qkv, const void* o, const void* d_o, const float* lse,
+                          float* dscratch, void* dqkv, int B, int S, int h, int dh, int bf,
+                          hipStream_t st);
+bool attention_mfma_supported(int S, int dh, int bf);
+int attention_fwd_mfma(const void* qkv, void* o, float* lse, int B, int S, int h, int dh,
+                       hipStream_t st);
+int attention_bwd_mfma(const void* qkv, const void* o, const void* d_o, const float* lse,
+                       float* dscratch, void* dqkv, int B, int S, int h, int dh, hipStream_t st);
+
+// ---- elementwise / reductions ----------------------------------------------------------------
+int embed_fwd(const int32_t* tok, const float* E, const float* Ppos, float* x, int B, int S, int d,
+              int V, hipStream_t st);
+int rmsnorm_fwd(const float* x, const float* g, void* y, float* rstd, int T, int d, float eps,
+                int out_bf16, hipStream_t st);
+// dx_out = (dx_in ? dx_in : 0) + rmsnorm_backward(dy); optional low-precision copy of dx_out;
+// dg = sum over rows of dy * xhat (uses partial[nblk*d] scratch, nblk = rmsnorm_bwd_blocks()).
+int rmsnorm_bwd_blocks(int T);
+int rmsnorm_bwd(const float* dy, const float* x, const float* rstd, const float* g,
+                const float* dx_in, float* dx_out, void* dx_lp, int lp_bf16, float* dg,
+                float* partial, int T, int d, hipStream_t st);
+int cross_entropy(const float* logits, const int32_t* tok, float* loss_row, void* dlogits,
+                  int dl_bf16, int B, int S, int V, hipStream_t st);
+int mean_rows(const float* loss_row, float* out, int T, hipStream_t st);
+// Orders each step's input positions by token id (see elementwise.hip); offset is
+// [n_steps][V+1], rank and pos are [n_steps][B*S].
+int embed_sort(const int32_t* tok, int n_steps, int B, int S, int V, int32_t* offset, int32_t* rank,
+               int32_t* pos, hipStream_t st);
+int embed_bwd(const int32_t* offset, const int32_t* pos, const float* dx, float* dE, float* dPpos,
+              int B, int S, int d, int V, hipStream_t st);
+int cast_copy(const float* src, void* dst, int64_t n, int dst_bf16, hipStream_t st);
+
+struct AdamArgs {
+  float lr, beta1, beta2, eps, wd, bc1, bc2;
+};
+int adamw(float* theta, const float* grad, float* m, float* v, bf16* lp, int64_t P,
+          int64_t P_decay, const AdamArgs& a, hipStream_t st);
+
+#define ALS_DN_MAX_GROUP 16
+struct DnGroup {
+  const float* theta_start[ALS_DN_MAX_GROUP];
+  float* theta_worker[ALS_DN_MAX_GROUP];
+  float* start_out[ALS_DN_MAX_GROUP];
+  bf16* lp_out[ALS_DN_MAX_GROUP];
+  int G;
+  int restart;
+  unsigned boundary_mask;  // bit j set: event j is an N-th event
+  float lr, beta, c_beta, cb_boundary, Nf;  // c*beta ; (1 - cN + c)*beta
+};
+int dn_group(float* theta, float* m, float* delta, const DnGroup& g, int64_t P, hipStream_t st);
+int restart_copy(const float* theta, float* master, float* start, bf16* lp, int64_t P,
+                 hipStream_t st);
+
+}  // namespace als

@@ -1,0 +1,532 @@
+// Context, arena carve-up and the orchestration of the hot path: a worker's local round
+// (inner loop of Alg. 1: forward, backward, AdamW) on that worker's stream, and the server's
+// sync() step (pseudo-gradient, Delayed Nesterov of Alg. 3, restart of Alg. 2) ordered
+// against the workers with events.
+#include "common.h"
+#include <math.h>
+#include <string.h>
+#include <new>
+#include <vector>
+
+using namespace als;
+
+namespace {
+
+struct Worker {
+  float *theta, *start, *adam_m, *adam_v, *grad;
+  bf16* lp;
+  std::vector<float*> x, xm, rstd1, rstd2, lse;
+  std::vector<void*> a, qkv, o, b, u, gl;
+  void* xf; float* rstdf; float* logits; void* dlogits; float* loss_row;
+  float *dxa, *dxb, *dtmp, *Dbuf, *partial;
+  void *dx_lp, *dff, *d_o, *dqkv;
+  float* losses_dev; float* losses_host;
+  int32_t *sort_offset, *sort_rank, *sort_pos;
+  float* splitk_ws; size_t splitk_bytes;
+  int64_t adam_n; int last_n;
+  hipStream_t stream; hipEvent_t done_ev, ready_ev;
+};
+
+}  // namespace
+
+struct als_ctx {
+  als_config cfg;
+  Layout L;
+  char* arena; size_t arena_bytes;
+  float *theta, *m, *delta;
+  int64_t t;
+  std::vector<Worker> w;
+  hipEvent_t server_ev;
+  bool bf; bool allow_mfma;
+  int T;
+};
+
+namespace {
+
+// Walks the arena handing out 256-byte aligned blocks; with base == nullptr it only counts.
+struct Carver {
+  char* base; size_t off;
+  void* take(size_t bytes) {
+    size_t a = (off + 255) & ~(size_t)255;
+    off = a + bytes;
+    return base ? (void*)(base + a) : nullptr;
+  }
+  float* f32(int64_t n) { return (float*)take((size_t)n * 4); }
+  void* act(int64_t n, bool bf) { return take((size_t)n * (bf ? 2 : 4)); }
+};
+
+void carve(als_ctx* c, Carver& cv) {
+  const als_config& g = c->cfg;
+  bool bf = g.dtype == ALS_DTYPE_BF16;
+  int64_t P = c->L.P, T = (int64_t)g.batch * g.seq_len, d = g.d_model, ff = g.d_ff, V = g.vocab;
+  int64_t BhS = (int64_t)g.batch * g.n_heads * g.seq_len;
+  c->theta = cv.f32(P); c->m = cv.f32(P); c->delta = cv.f32(P);
+  c->w.resize(g.n_workers);
+  for (Worker& w : c->w) {
+    w.theta = cv.f32(P); w.start = cv.f32(P); w.adam_m = cv.f32(P); w.adam_v = cv.f32(P);
+    w.grad = cv.f32(P);
+    w.lp = bf ? (bf16*)cv.take((size_t)P * 2) : nullptr;
+    int L = g.n_layers;
+    w.x.resize(L + 1); w.xm.resize(L); w.rstd1.resize(L); w.rstd2.resize(L); w.lse.resize(L);
+    w.a.resize(L); w.qkv.resize(L); w.o.resize(L); w.b.resize(L); w.u.resize(L); w.gl.resize(L);
+    for (int l = 0; l <= L; l++) w.x[l] = cv.f32(T * d);
+    for (int l = 0; l < L; l++) {
+      w.xm[l] = cv.f32(T * d); w.rstd1[l] = cv.f32(T); w.rstd2[l] = cv.f32(T); w.lse[l] = cv.f32(BhS);
+      w.a[l] = cv.act(T * d, bf); w.qkv[l] = cv.act(T * 3 * d, bf); w.o[l] = cv.act(T * d, bf);
+      w.b[l] = cv.act(T * d, bf); w.u[l] = cv.act(T * ff, bf); w.gl[l] = cv.act(T * ff, bf);
+    }
+    w.xf = cv.act(T * d, bf); w.rstdf = cv.f32(T);
+    w.logits = cv.f32(T * V); w.dlogits = cv.act(T * V, bf); w.loss_row = cv.f32(T);
+    w.dxa = cv.f32(T * d); w.dxb = cv.f32(T * d); w.dtmp = cv.f32(T * d); w.Dbuf = cv.f32(BhS);
+    w.partial = cv.f32((int64_t)rmsnorm_bwd_blocks((int)T) * d);
+    w.dx_lp = cv.act(T * d, bf); w.dff = cv.act(T * ff, bf); w.d_o = cv.act(T * d, bf);
+    w.dqkv = cv.act(T * 3 * d, bf);
+    w.losses_dev = cv.f32(g.max_local_steps);
+    w.sort_offset = (int32_t*)cv.take((size_t)g.max_local_steps * (V + 1) * 4);
+    w.sort_rank = (int32_t*)cv.take((size_t)g.max_local_steps * T * 4);
+    w.sort_pos = (int32_t*)cv.take((size_t)g.max_local_steps * T * 4);
+    // split-K partials of the weight-gradient GEMMs: up to 16 copies of the largest layer
+    // matrix, capped at 64 MiB
+    {
+      int64_t big = d * (ff > 3 * d ? ff : 3 * d);
+      size_t want = (size_t)big * 4 * 16;
+      w.splitk_bytes = bf ? (want < ((size_t)64 << 20) ? want : ((size_t)64 << 20)) : 0;
+      w.splitk_ws = w.splitk_bytes ? (float*)cv.take(w.splitk_bytes) : nullptr;
+    }
+  }
+}
+
+GemmDesc desc(const als_ctx* c, const void* A, int a_layout, int64_t lda, const void* B, int b_layout,
+              int64_t ldb, int M, int N, int K, void* C, int64_t ldc, bool c_act) {
+  GemmDesc g;
+  memset(&g, 0, sizeof g);
+  g.A = A; g.B = B; g.M = M; g.N = N; g.K = K; g.a_layout = a_layout; g.b_layout = b_layout;
+  g.lda = lda; g.ldb = ldb; g.in_bf16 = c->bf; g.C = C; g.ldc = ldc; g.c_bf16 = c_act && c->bf;
+  g.epi = EPI_STORE;
+  return g;
+}
+
+// weight-gradient GEMM: X^T dY into the flat fp32 gradient, with the worker's split-K scratch
+GemmDesc desc_dw(const als_ctx* c, const Worker& w, const void* X, int64_t ldx, const void* dY, int64_t ldy,
+                 int M, int N, int K, float* out) {
+  GemmDesc g = desc(c, X, 1, ldx, dY, 0, ldy, M, N, K, out, N, false);
+  g.ws = w.splitk_ws; g.ws_bytes = w.splitk_bytes;
+  return g;
+}
+
+#define RUN(expr) do { int rc_ = (expr); if (rc_) return rc_; } while (0)
+
+// Weight operand of a GEMM: the bf16 working copy in bf16 mode, the fp32 master otherwise.
+inline const void* wptr(const als_ctx* c, const Worker& w, int64_t off) {
+  return c->bf ? (const void*)(w.lp + off) : (const void*)(w.theta + off);
+}
+
+int forward(als_ctx* c, Worker& w, const int32_t* tok, float* loss_out) {
+  const als_config& g = c->cfg;
+  const Layout& L = c->L;
+  hipStream_t st = w.stream;
+  int T = c->T, d = g.d_model, ff = g.d_ff, V = g.vocab, B = g.batch, S = g.seq_len, h = g.n_heads;
+  bool mf = c->allow_mfma;
+  float eps = (float)g.norm_eps;
+  RUN(embed_fwd(tok, w.theta + L.E, w.theta + L.Ppos, w.x[0], B, S, d, V, st));
+  for (int l = 0; l < g.n_layers; l++) {
+    RUN(rmsnorm_fwd(w.x[l], w.theta + L.g1[l], w.a[l], w.rstd1[l], T, d, eps, c->bf, st));
+    RUN(gemm(desc(c, w.a[l], 0, d, wptr(c, w, L.Wqkv[l]), 0, 3 * d, T, 3 * d, d, w.qkv[l], 3 * d, true), mf, st));
+    if (mf && attention_mfma_supported(S, d / h, c->bf))
+      RUN(attention_fwd_mfma(w.qkv[l], w.o[l], w.lse[l], B, S, h, d / h, st));
+    else
+      RUN(attention_fwd_generic(w.qkv[l], w.o[l], w.lse[l], B, S, h, d / h, c->bf, st));
+    GemmDesc po = desc(c, w.o[l], 0, d, wptr(c, w, L.Wo[l]), 0, d, T, d, d, w.xm[l], d, false);
+    po.epi = EPI_RESID; po.R = w.x[l]; po.ldr = d;
+    RUN(gemm(po, mf, st));
+    RUN(rmsnorm_fwd(w.xm[l], w.theta + L.g2[l], w.b[l], w.rstd2[l], T, d, eps, c->bf, st));
+    GemmDesc f1 = desc(c, w.b[l], 0, d, wptr(c, w, L.W1[l]), 0, ff, T, ff, d, w.u[l], ff, true);
+    f1.epi = EPI_GELU; f1.C2 = w.gl[l];
+    RUN(gemm(f1, mf, st));
+    GemmDesc f2 = desc(c, w.gl[l], 0, ff, wptr(c, w, L.W2[l]), 0, d, T, d, ff, w.x[l + 1], d, false);
+    f2.epi = EPI_RESID; f2.R = w.xm[l]; f2.ldr = d;
+    RUN(gemm(f2, mf, st));
+  }
+  RUN(rmsnorm_fwd(w.x[g.n_layers], w.theta + L.gf, w.xf, w.rstdf, T, d, eps, c->bf, st));
+  RUN(gemm(desc(c, w.xf, 0, d, wptr(c, w, L.Wout), 0, V, T, V, d, w.logits, V, false), mf, st));
+  RUN(cross_entropy(w.logits, tok, w.loss_row, w.dlogits, c->bf, B, S, V, st));
+  RUN(mean_rows(w.loss_row, loss_out, T, st));
+  return ALS_OK;
+}
+
+int backward(als_ctx* c, Worker& w, int slot) {
+  const als_config& g = c->cfg;
+  const Layout& L = c->L;
+  hipStream_t st = w.stream;
+  int T = c->T, d = g.d_model, ff = g.d_ff, V = g.vocab, B = g.batch, S = g.seq_len, h = g.n_heads;
+  bool mf = c->allow_mfma;
+  int nl = g.n_layers;
+  // output matrix and final norm
+  RUN(gemm(desc_dw(c, w, w.xf, d, w.dlogits, V, d, V, T, w.grad + L.Wout), mf, st));
+  RUN(gemm(desc(c, w.dlogits, 0, V, wptr(c, w, L.Wout), 1, V, T, d, V, w.dtmp, d, false), mf, st));
+  RUN(rmsnorm_bwd(w.dtmp, w.x[nl], w.rstdf, w.theta + L.gf, nullptr, w.dxa, w.dx_lp, c->bf,
+                  w.grad + L.gf, w.partial, T, d, st));
+  for (int l = nl - 1; l >= 0; l--) {
+    // feed-forward block: x_next = xm + gelu(b W1) W2
+    RUN(gemm(desc_dw(c, w, w.gl[l], ff, w.dx_lp, d, ff, d, T, w.grad + L.W2[l]), mf, st));
+    GemmDesc du = desc(c, w.dx_lp, 0, d, wptr(c, w, L.W2[l]), 1, d, T, ff, d, w.dff, ff, true);
+    du.epi = EPI_DGELU; du.U = w.u[l];
+    RUN(gemm(du, mf, st));
+    RUN(gemm(desc_dw(c, w, w.b[l], d, w.dff, ff, d, ff, T, w.grad + L.W1[l]), mf, st));
+    RUN(gemm(desc(c, w.dff, 0, ff, wptr(c, w, L.W1[l]), 1, ff, T, d, ff, w.dtmp, d, false), mf, st));
+    RUN(rmsnorm_bwd(w.dtmp, w.xm[l], w.rstd2[l], w.theta + L.g2[l], w.dxa, w.dxb, w.dx_lp, c->bf,
+                    w.grad + L.g2[l], w.partial, T, d, st));
+    // attention block: xm = x + attn(a Wqkv) Wo
+    RUN(gemm(desc_dw(c, w, w.o[l], d, w.dx_lp, d, d, d, T, w.grad + L.Wo[l]), mf, st));
+    RUN(gemm(desc(c, w.dx_lp, 0, d, wptr(c, w, L.Wo[l]), 1, d, T, d, d, w.d_o, d, true), mf, st));
+    if (mf && attention_mfma_supported(S, d / h, c->bf))
+      RUN(attention_bwd_mfma(w.qkv[l], w.o[l], w.d_o, w.lse[l], w.Dbuf, w.dqkv, B, S, h, d / h, st));
+    else
+      RUN(attention_bwd_generic(w.qkv[l], w.o[l], w.d_o, w.lse[l], w.Dbuf, w.dqkv, B, S, h, d / h, c->bf, st));
+    RUN(gemm(desc_dw(c, w, w.a[l], d, w.dqkv, 3 * d, d, 3 * d, T, w.grad + L.Wqkv[l]), mf, st));
+    RUN(gemm(desc(c, w.dqkv, 0, 3 * d, wptr(c, w, L.Wqkv[l]), 1, 3 * d, T, d, 3 * d, w.dtmp, d, false), mf, st));
+    RUN(rmsnorm_bwd(w.dtmp, w.x[l], w.rstd1[l], w.theta + L.g1[l], w.dxb, w.dxa, w.dx_lp, c->bf,
+                    w.grad + L.g1[l], w.partial, T, d, st));
+  }
+  RUN(embed_bwd(w.sort_offset + (int64_t)slot * (V + 1), w.sort_pos + (int64_t)slot * T, w.dxa,
+                w.grad + L.E, w.grad + L.Ppos, B, S, d, V, st));
+  return ALS_OK;
+}
+
+int check_ctx_worker(als_ctx* ctx, int worker) {
+  if (!ctx) return set_error(ALS_ERR_INVALID, "context is null");
+  if (worker < 0 || worker >= (int)ctx->w.size()) return set_error(ALS_ERR_INVALID, "worker %d out of range", worker);
+  return ALS_OK;
+}
+
+int sync_all(als_ctx* ctx) {
+  for (Worker& w : ctx->w) ALS_HIP(hipStreamSynchronize(w.stream));
+  return ALS_OK;
+}
+
+}  // namespace
+
+extern "C" size_t als_arena_bytes(const als_config* cfg) {
+  if (validate_config(cfg)) return 0;
+  als_ctx tmp;
+  tmp.cfg = *cfg;
+  make_layout(*cfg, &tmp.L);
+  Carver cv{nullptr, 0};
+  carve(&tmp, cv);
+  return cv.off + 256;
+}
+
+extern "C" int als_init(const als_config* cfg, void* arena, size_t arena_bytes, const float* theta0,
+                        void* const* streams, int n_streams, als_ctx** out) {
+  int rc = validate_config(cfg);
+  if (rc) return rc;
+  if (!arena || !theta0 || !out || !streams || n_streams < 1)
+    return set_error(ALS_ERR_INVALID, "als_init: null argument or no stream");
+  if ((uintptr_t)arena % 256) return set_error(ALS_ERR_ARENA, "arena must be 256-byte aligned");
+  size_t need = als_arena_bytes(cfg);
+  if (arena_bytes < need) return set_error(ALS_ERR_ARENA, "arena too small: %zu bytes given, %zu needed", arena_bytes, need);
+  als_ctx* c = new (std::nothrow) als_ctx();
+  if (!c) return set_error(ALS_ERR_INVALID, "out of host memory");
+  c->cfg = *cfg;
+  make_layout(*cfg, &c->L);
+  c->arena = (char*)arena; c->arena_bytes = arena_bytes;
+  c->bf = cfg->dtype == ALS_DTYPE_BF16;
+  c->allow_mfma = c->bf && !(cfg->flags & 1);
+  c->T = cfg->batch * cfg->seq_len;
+  c->t = 0;
+  Carver cv{(char*)arena, 0};
+  carve(c, cv);
+  int64_t P = c->L.P;
+  hipStream_t s0 = (hipStream_t)streams[0];
+  c->server_ev = nullptr;
+  for (Worker& w : c->w) { w.done_ev = nullptr; w.ready_ev = nullptr; w.losses_host = nullptr; }
+  auto fail = [&](int code) { als_destroy(c); return code; };
+  if (hipEventCreateWithFlags(&c->server_ev, hipEventDisableTiming) != hipSuccess)
+    return fail(set_error(ALS_ERR_HIP, "hipEventCreate failed"));
+  if (hipMemcpyAsync(c->theta, theta0, (size_t)P * 4, hipMemcpyHostToDevice, s0) != hipSuccess ||
+      hipMemsetAsync(c->m, 0, (size_t)P * 4, s0) != hipSuccess ||
+      hipMemsetAsync(c->delta, 0, (size_t)P * 4, s0) != hipSuccess ||
+      hipStreamSynchronize(s0) != hipSuccess)
+    return fail(set_error(ALS_ERR_HIP, "als_init: copying theta0 failed: %s", hipGetErrorString(hipGetLastError())));
+  for (size_t i = 0; i < c->w.size(); i++) {
+    Worker& w = c->w[i];
+    w.stream = (hipStream_t)streams[i % n_streams];
+    w.adam_n = 0; w.last_n = 0;
+    if (hipEventCreateWithFlags(&w.done_ev, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&w.ready_ev, hipEventDisableTiming) != hipSuccess ||
+        hipHostMalloc((void**)&w.losses_host, (size_t)cfg->max_local_steps * 4, hipHostMallocDefault) != hipSuccess)
+      return fail(set_error(ALS_ERR_HIP, "als_init: event or pinned-buffer creation failed"));
+    if (hipMemsetAsync(w.adam_m, 0, (size_t)P * 4, w.stream) != hipSuccess ||
+        hipMemsetAsync(w.adam_v, 0, (size_t)P * 4, w.stream) != hipSuccess ||
+        hipMemsetAsync(w.grad, 0, (size_t)P * 4, w.stream) != hipSuccess)
+      return fail(set_error(ALS_ERR_HIP, "als_init: clearing optimiser state failed"));
+    rc = restart_copy(c->theta, w.theta, w.start, w.lp, P, w.stream);
+    if (rc) return fail(rc);
+    if (hipEventRecord(w.ready_ev, w.stream) != hipSuccess || hipEventRecord(w.done_ev, w.stream) != hipSuccess)
+      return fail(set_error(ALS_ERR_HIP, "als_init: hipEventRecord failed"));
+  }
+  if (hipEventRecord(c->server_ev, s0) != hipSuccess) return fail(set_error(ALS_ERR_HIP, "hipEventRecord failed"));
+  rc = sync_all(c);
+  if (rc) return fail(rc);
+  *out = c;
+  return ALS_OK;
+}
+
+extern "C" int als_destroy(als_ctx* c) {
+  if (!c) return ALS_OK;
+  for (Worker& w : c->w) {
+    if (w.stream) (void)hipStreamSynchronize(w.stream);
+    if (w.done_ev) (void)hipEventDestroy(w.done_ev);
+    if (w.ready_ev) (void)hipEventDestroy(w.ready_ev);
+    if (w.losses_host) (void)hipHostFree(w.losses_host);
+  }
+  if (c->server_ev) (void)hipEventDestroy(c->server_ev);
+  delete c;
+  return ALS_OK;
+}
+
+extern "C" int als_worker_local_steps(als_ctx* ctx, int worker, int n_steps, const int32_t* tokens,
+                                      const float* lr_host, float* loss_host) {
+  int rc = check_ctx_worker(ctx, worker);
+  if (rc) return rc;
+  const als_config& g = ctx->cfg;
+  if (n_steps < 0 || n_steps > g.max_local_steps)
+    return set_error(ALS_ERR_INVALID, "n_steps %d outside 0..max_local_steps=%d", n_steps, g.max_local_steps);
+  if (n_steps > 0 && (!tokens || !lr_host)) return set_error(ALS_ERR_INVALID, "tokens_dev and lr_host must be non-null");
+  Worker& w = ctx->w[worker];
+  ALS_HIP(hipStreamWaitEvent(w.stream, w.ready_ev, 0));
+  int64_t per = (int64_t)g.batch * (g.seq_len + 1);
+  RUN(embed_sort(tokens, n_steps, g.batch, g.seq_len, g.vocab, w.sort_offset, w.sort_rank, w.sort_pos, w.stream));
+  for (int s = 0; s < n_steps; s++) {
+    const int32_t* tok = tokens + (int64_t)s * per;
+    RUN(forward(ctx, w, tok, w.losses_dev + s));
+    RUN(backward(ctx, w, s));
+    w.adam_n += 1;
+    AdamArgs a;
+    a.lr = lr_host[s];
+    a.beta1 = (float)g.adam_beta1; a.beta2 = (float)g.adam_beta2; a.eps = (float)g.adam_eps;
+    a.wd = (float)g.weight_decay;
+    a.bc1 = (float)(1.0 - pow(g.adam_beta1, (double)w.adam_n));
+    a.bc2 = (float)(1.0 - pow(g.adam_beta2, (double)w.adam_n));
+    RUN(adamw(w.theta, w.grad, w.adam_m, w.adam_v, w.lp, ctx->L.P, ctx->L.P_decay, a, w.stream));
+  }
+  w.last_n = n_steps;
+  if (n_steps > 0)
+    ALS_HIP(hipMemcpyAsync(w.losses_host, w.losses_dev, (size_t)n_steps * 4, hipMemcpyDeviceToHost, w.stream));
+  ALS_HIP(hipEventRecord(w.done_ev, w.stream));
+  if (loss_host) {
+    ALS_HIP(hipStreamSynchronize(w.stream));
+    memcpy(loss_host, w.losses_host, (size_t)n_steps * 4);
+  }
+  return ALS_OK;
+}
+
+extern "C" int als_worker_loss_grad(als_ctx* ctx, int worker, const int32_t* tokens, float* loss_host) {
+  int rc = check_ctx_worker(ctx, worker);
+  if (rc) return rc;
+  if (!tokens || !loss_host) return set_error(ALS_ERR_INVALID, "tokens_dev and loss_host must be non-null");
+  Worker& w = ctx->w[worker];
+  ALS_HIP(hipStreamWaitEvent(w.stream, w.ready_ev, 0));
+  RUN(embed_sort(tokens, 1, ctx->cfg.batch, ctx->cfg.seq_len, ctx->cfg.vocab, w.sort_offset, w.sort_rank,
+                 w.sort_pos, w.stream));
+  RUN(forward(ctx, w, tokens, w.losses_dev));
+  RUN(backward(ctx, w, 0));
+  ALS_HIP(hipMemcpyAsync(w.losses_host, w.losses_dev, 4, hipMemcpyDeviceToHost, w.stream));
+  ALS_HIP(hipEventRecord(w.done_ev, w.stream));
+  ALS_HIP(hipStreamSynchronize(w.stream));
+  *loss_host = w.losses_host[0];
+  return ALS_OK;
+}
+
+extern "C" int als_outer_apply_dn(als_ctx* ctx, const int32_t* workers, int n_group, int restart_flag) {
+  if (!ctx || !workers) return set_error(ALS_ERR_INVALID, "null argument");
+  int k = (int)ctx->w.size();
+  if (n_group < 1 || n_group > k) return set_error(ALS_ERR_INVALID, "n_group %d outside 1..k", n_group);
+  unsigned long long seen = 0;
+  for (int j = 0; j < n_group; j++) {
+    if (workers[j] < 0 || workers[j] >= k) return set_error(ALS_ERR_INVALID, "worker %d out of range", workers[j]);
+    if (seen >> workers[j] & 1ull) return set_error(ALS_ERR_INVALID, "worker %d listed twice", workers[j]);
+    seen |= 1ull << workers[j];
+  }
+  const als_config& g = ctx->cfg;
+  hipStream_t st = ctx->w[workers[0]].stream;
+  ALS_HIP(hipStreamWaitEvent(st, ctx->server_ev, 0));
+  for (int j = 0; j < n_group; j++) ALS_HIP(hipStreamWaitEvent(st, ctx->w[workers[j]].done_ev, 0));
+  int64_t P = ctx->L.P;
+  bool fused_restart = restart_flag && n_group <= ALS_DN_MAX_GROUP;
+  for (int j0 = 0; j0 < n_group; j0 += ALS_DN_MAX_GROUP) {
+    DnGroup dg;
+    memset(&dg, 0, sizeof dg);
+    dg.G = n_group - j0 < ALS_DN_MAX_GROUP ? n_group - j0 : ALS_DN_MAX_GROUP;
+    dg.restart = fused_restart ? 1 : 0;
+    for (int j = 0; j < dg.G; j++) {
+      Worker& w = ctx->w[workers[j0 + j]];
+      dg.theta_start[j] = w.start; dg.theta_worker[j] = w.theta; dg.start_out[j] = w.start;
+      dg.lp_out[j] = w.lp;
+      if ((ctx->t + j + 1) % g.dn_N == 0) dg.boundary_mask |= 1u << j;
+    }
+    dg.lr = (float)g.outer_lr; dg.beta = (float)g.outer_beta;
+    dg.c_beta = (float)(g.dn_c * g.outer_beta);
+    dg.cb_boundary = (float)((1.0 - g.dn_c * g.dn_N + g.dn_c) * g.outer_beta);
+    dg.Nf = (float)g.dn_N;
+    RUN(dn_group(ctx->theta, ctx->m, ctx->delta, dg, P, st));
+    ctx->t += dg.G;
+  }
+  if (restart_flag && !fused_restart)
+    for (int j = 0; j < n_group; j++) {
+      Worker& w = ctx->w[workers[j]];
+      RUN(restart_copy(ctx->theta, w.theta, w.start, w.lp, P, st));
+    }
+  ALS_HIP(hipEventRecord(ctx->server_ev, st));
+  // Whatever touches these replicas next (their local steps, or a later sync) is ordered
+  // after this call.
+  for (int j = 0; j < n_group; j++) {
+    ALS_HIP(hipEventRecord(ctx->w[workers[j]].ready_ev, st));
+    ALS_HIP(hipEventRecord(ctx->w[workers[j]].done_ev, st));
+  }
+  return ALS_OK;
+}
+
+extern "C" int als_sync(als_ctx* ctx, int worker) {
+  if (!ctx) return set_error(ALS_ERR_INVALID, "context is null");
+  if (worker < 0) return sync_all(ctx);
+  int rc = check_ctx_worker(ctx, worker);
+  if (rc) return rc;
+  ALS_HIP(hipStreamSynchronize(ctx->w[worker].stream));
+  return ALS_OK;
+}
+
+static float* vector_ptr(als_ctx* ctx, int which, int worker) {
+  switch (which) {
+    case ALS_VEC_THETA: return ctx->theta;
+    case ALS_VEC_MOMENTUM: return ctx->m;
+    case ALS_VEC_DELTA: return ctx->delta;
+    default: break;
+  }
+  if (worker < 0 || worker >= (int)ctx->w.size()) return nullptr;
+  Worker& w = ctx->w[worker];
+  switch (which) {
+    case ALS_VEC_WORKER_THETA: return w.theta;
+    case ALS_VEC_WORKER_START: return w.start;
+    case ALS_VEC_ADAM_M: return w.adam_m;
+    case ALS_VEC_ADAM_V: return w.adam_v;
+    case ALS_VEC_GRAD: return w.grad;
+    default: return nullptr;
+  }
+}
+
+extern "C" int als_get_vector(als_ctx* ctx, int which, int worker, float* host_out) {
+  if (!ctx || !host_out) return set_error(ALS_ERR_INVALID, "null argument");
+  float* p = vector_ptr(ctx, which, worker);
+  if (!p) return set_error(ALS_ERR_INVALID, "unknown vector %d / worker %d", which, worker);
+  RUN(sync_all(ctx));
+  ALS_HIP(hipMemcpy(host_out, p, (size_t)ctx->L.P * 4, hipMemcpyDeviceToHost));
+  return ALS_OK;
+}
+
+extern "C" int als_set_vector(als_ctx* ctx, int which, int worker, const float* host_in) {
+  if (!ctx || !host_in) return set_error(ALS_ERR_INVALID, "null argument");
+  float* p = vector_ptr(ctx, which, worker);
+  if (!p) return set_error(ALS_ERR_INVALID, "unknown vector %d / worker %d", which, worker);
+  RUN(sync_all(ctx));
+  ALS_HIP(hipMemcpy(p, host_in, (size_t)ctx->L.P * 4, hipMemcpyHostToDevice));
+  if (which == ALS_VEC_WORKER_THETA && ctx->bf) {
+    Worker& w = ctx->w[worker];
+    RUN(cast_copy(w.theta, w.lp, ctx->L.P, 1, w.stream));
+    ALS_HIP(hipStreamSynchronize(w.stream));
+  }
+  return ALS_OK;
+}
+
+extern "C" int als_get_losses(als_ctx* ctx, int worker, float* host_out, int n) {
+  int rc = check_ctx_worker(ctx, worker);
+  if (rc) return rc;
+  Worker& w = ctx->w[worker];
+  if (!host_out || n < 0 || n > w.last_n) return set_error(ALS_ERR_INVALID, "n outside 0..%d", w.last_n);
+  ALS_HIP(hipStreamSynchronize(w.stream));
+  memcpy(host_out, w.losses_host, (size_t)n * 4);
+  return ALS_OK;
+}
+
+extern "C" int64_t als_server_t(als_ctx* ctx) { return ctx ? ctx->t : -1; }
+extern "C" int64_t als_worker_adam_steps(als_ctx* ctx, int worker) {
+  if (check_ctx_worker(ctx, worker)) return -1;
+  return ctx->w[worker].adam_n;
+}
+
+// ---- stand-alone kernel entry points ---------------------------------------------------------
+extern "C" int als_k_dn_group(float* theta, float* m, float* delta, float* const* theta_start,
+                              float* const* theta_worker, void* const* bf16_worker, int G, int64_t P,
+                              int N, int64_t t0, double outer_lr, double beta, double c, int restart,
+                              void* stream) {
+  if (G < 1 || G > ALS_DN_MAX_GROUP || P < 0 || N < 1 || t0 < 0) return set_error(ALS_ERR_INVALID, "G, P, N or t0 out of range");
+  if (!(c >= 0 && c <= 1.0 / N + 1e-12)) return set_error(ALS_ERR_INVALID, "c must lie in [0, 1/N]");
+  if (P == 0) return ALS_OK;
+  if (!theta || !m || !delta || !theta_start || !theta_worker) return set_error(ALS_ERR_INVALID, "null argument");
+  DnGroup dg;
+  memset(&dg, 0, sizeof dg);
+  dg.G = G; dg.restart = restart ? 1 : 0;
+  for (int j = 0; j < G; j++) {
+    if (!theta_start[j] || !theta_worker[j]) return set_error(ALS_ERR_INVALID, "null worker vector");
+    dg.theta_start[j] = theta_start[j]; dg.theta_worker[j] = theta_worker[j];
+    dg.start_out[j] = theta_start[j];
+    dg.lp_out[j] = bf16_worker ? (bf16*)bf16_worker[j] : nullptr;
+    if ((t0 + j + 1) % N == 0) dg.boundary_mask |= 1u << j;
+  }
+  dg.lr = (float)outer_lr; dg.beta = (float)beta; dg.c_beta = (float)(c * beta);
+  dg.cb_boundary = (float)((1.0 - c * N + c) * beta); dg.Nf = (float)N;
+  return dn_group(theta, m, delta, dg, P, (hipStream_t)stream);
+}
+
+extern "C" int als_k_adamw(float* theta, const float* grad, float* m, float* v, void* bf16_out, int64_t P,
+                           int64_t P_decay, int64_t step, double lr, double beta1, double beta2,
+                           double eps, double wd, void* stream) {
+  if (P < 0 || P_decay < 0 || step < 1) return set_error(ALS_ERR_INVALID, "P, P_decay or step out of range");
+  if (P == 0) return ALS_OK;
+  if (!theta || !grad || !m || !v) return set_error(ALS_ERR_INVALID, "null argument");
+  AdamArgs a;
+  a.lr = (float)lr; a.beta1 = (float)beta1; a.beta2 = (float)beta2; a.eps = (float)eps; a.wd = (float)wd;
+  a.bc1 = (float)(1.0 - pow(beta1, (double)step));
+  a.bc2 = (float)(1.0 - pow(beta2, (double)step));
+  return adamw(theta, grad, m, v, (bf16*)bf16_out, P, P_decay, a, (hipStream_t)stream);
+}
+
+extern "C" int als_k_gemm(const void* A, const void* B, void* C, int M, int N, int K, int a_layout,
+                          int b_layout, int in_dtype, int out_dtype, int use_mfma, void* ws_dev,
+                          size_t ws_bytes, void* stream) {
+  if (!A || !B || !C) return set_error(ALS_ERR_INVALID, "null argument");
+  GemmDesc g;
+  memset(&g, 0, sizeof g);
+  g.A = A; g.B = B; g.C = C; g.M = M; g.N = N; g.K = K; g.a_layout = a_layout; g.b_layout = b_layout;
+  g.lda = a_layout == 0 ? K : M; g.ldb = b_layout == 0 ? N : K; g.ldc = N;
+  g.in_bf16 = in_dtype == ALS_DTYPE_BF16; g.c_bf16 = out_dtype == ALS_DTYPE_BF16; g.epi = EPI_STORE;
+  g.ws = (float*)ws_dev; g.ws_bytes = ws_dev ? ws_bytes : 0;
+  if (use_mfma) {
+    if (!gemm_mfma_supported(g)) return set_error(ALS_ERR_INVALID, "shape/dtype not supported by the MFMA GEMM");
+    return gemm_mfma(g, (hipStream_t)stream);
+  }
+  return gemm_generic(g, (hipStream_t)stream);
+}
+
+extern "C" int als_k_attention_fwd(const void* qkv, void* o, float* lse, int B, int S, int h, int dh,
+                                   int dtype, int use_mfma, void* stream) {
+  if (!qkv || !o || !lse) return set_error(ALS_ERR_INVALID, "null argument");
+  int bf = dtype == ALS_DTYPE_BF16;
+  if (use_mfma) {
+    if (!attention_mfma_supported(S, dh, bf)) return set_error(ALS_ERR_INVALID, "shape/dtype not supported by the MFMA attention");
+    return attention_fwd_mfma(qkv, o, lse, B, S, h, dh, (hipStream_t)stream);
+  }
+  return attention_fwd_generic(qkv, o, lse, B, S, h, dh, bf, (hipStream_t)stream);
+}
+
+extern "C" int als_k_attention_bwd(const void* qkv, const void* o, const void* d_o, const float* lse,
+                                   float* dscratch, void* dqkv, int B, int S, int h, int dh, int dtype,
+                                   int use_mfma, void* stream) {
+  if (!qkv || !o || !d_o || !lse || !dscratch || !dqkv) return set_error(ALS_ERR_INVALID, "null argument");
+  int bf = dtype == ALS_DTYPE_BF16;
+  if (use_mfma) {
+    if (!attention_mfma_supported(S, dh, bf)) return set_error(ALS_ERR_INVALID, "shape/dtype not supported by the MFMA attention");
+    return attention_bwd_mfma(qkv, o, d_o, lse, dscratch, dqkv, B, S, h, dh, (hipStream_t)stream);
+  }
+  return attention_bwd_generic(qkv, o, d_o, lse, dscratch, dqkv, B, S, h, dh, bf, (hipStream_t)stream);
+}

@@ -1,0 +1,614 @@
+// HBM-bound kernels of the hot path: fused AdamW (inner optimiser), fused pseudo-gradient +
+// Delayed Nesterov event(s) + worker restart (Alg. 3 and the restart of Alg. 2), embedding,
+// RMSNorm, softmax cross-entropy and the small reductions around them.
+#include "common.h"
+#include <math.h>
+
+namespace als {
+
+static inline int blocks_for(int64_t n_items, int per_block, int cap) {
+  int64_t b = (n_items + per_block - 1) / per_block;
+  if (b < 1) b = 1;
+  if (b > cap) b = cap;
+  return (int)b;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+__device__ __forceinline__ void store_bf16x4(bf16* p, float4 v) {
+  bf16x4 o;
+  o[0] = (bf16)v.x; o[1] = (bf16)v.y; o[2] = (bf16)v.z; o[3] = (bf16)v.w;
+  *reinterpret_cast<bf16x4*>(p) = o;
+}
+
+// ------------------------------------------------------------------------------------------
+// AdamW, one pass over the flat vectors: reads grad, theta, m, v; writes theta, m, v and the
+// bf16 working copy.  16 + 12 (+2) bytes per parameter.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ float adam_one(float& th, float g, float& m, float& v, bool decay,
+                                          const AdamArgs& a) {
+  m = a.beta1 * m + (1.0f - a.beta1) * g;
+  v = a.beta2 * v + (1.0f - a.beta2) * g * g;
+  float mhat = m / a.bc1;
+  float vhat = v / a.bc2;
+  float upd = mhat / (sqrtf(vhat) + a.eps);
+  if (decay) upd += a.wd * th;
+  th -= a.lr * upd;
+  return th;
+}
+
+__global__ __launch_bounds__(256) void adamw_kernel(float* __restrict__ theta,
+                                                    const float* __restrict__ grad,
+                                                    float* __restrict__ m, float* __restrict__ v,
+                                                    bf16* __restrict__ lp, int64_t n4,
+                                                    int64_t decay4, AdamArgs a) {
+  int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+    float4 th = reinterpret_cast<float4*>(theta)[i];
+    float4 g = reinterpret_cast<const float4*>(grad)[i];
+    float4 mm = reinterpret_cast<float4*>(m)[i];
+    float4 vv = reinterpret_cast<float4*>(v)[i];
+    bool dec = i < decay4;
+    adam_one(th.x, g.x, mm.x, vv.x, dec, a);
+    adam_one(th.y, g.y, mm.y, vv.y, dec, a);
+    adam_one(th.z, g.z, mm.z, vv.z, dec, a);
+    adam_one(th.w, g.w, mm.w, vv.w, dec, a);
+    reinterpret_cast<float4*>(theta)[i] = th;
+    reinterpret_cast<float4*>(m)[i] = mm;
+    reinterpret_cast<float4*>(v)[i] = vv;
+    if (lp) store_bf16x4(lp + 4 * i, th);
+  }
+}
+
+__global__ void adamw_tail_kernel(float* theta, const float* grad, float* m, float* v, bf16* lp,
+                                  int64_t begin, int64_t P, int64_t P_decay, AdamArgs a) {
+  int64_t i = begin + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= P) return;
+  float th = theta[i], mm = m[i], vv = v[i];
+  adam_one(th, grad[i], mm, vv, i < P_decay, a);
+  theta[i] = th; m[i] = mm; v[i] = vv;
+  if (lp) lp[i] = (bf16)th;
+}
+
+int adamw(float* theta, const float* grad, float* m, float* v, bf16* lp, int64_t P,
+          int64_t P_decay, const AdamArgs& a, hipStream_t st) {
+  if (P <= 0) return ALS_OK;
+  // the vector body covers whole float4 groups that do not straddle the decay boundary
+  int64_t n4 = 0, decay4 = 0;
+  if (P_decay % 4 == 0 || P_decay >= P) {
+    n4 = P / 4;
+    decay4 = P_decay >= P ? n4 : P_decay / 4;
+  }
+  if (n4 > 0) {
+    int blocks = blocks_for(n4, 256, 256 * 16);
+    hipLaunchKernelGGL(adamw_kernel, dim3(blocks), dim3(256), 0, st, theta, grad, m, v, lp, n4,
+                       decay4, a);
+    ALS_CHECK_LAUNCH();
+  }
+  int64_t begin = n4 * 4;
+  if (begin < P) {
+    int blocks = blocks_for(P - begin, 256, 1 << 30);
+    hipLaunchKernelGGL(adamw_tail_kernel, dim3(blocks), dim3(256), 0, st, theta, grad, m, v, lp,
+                       begin, P, P_decay, a);
+    ALS_CHECK_LAUNCH();
+  }
+  return ALS_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Pseudo-gradient + Delayed Nesterov for a group of G workers in one pass, optionally fused
+// with the restart copy.  Per element, in event order j = 0..G-1:
+//   g = theta_start_j - theta_worker_j ; Delta += g
+//   N-th event:  m = beta m + Delta/N ; theta -= eps ((1 - cN + c) beta m + g/N) ; Delta = 0
+//   otherwise:   theta -= eps (c beta m + g/N)
+// ------------------------------------------------------------------------------------------
+template <int VEC>
+struct Vec;
+template <>
+struct Vec<4> { typedef float4 T; };
+template <>
+struct Vec<1> { typedef float T; };
+
+__device__ __forceinline__ void dn_event_scalar(float& th, float& mm, float& de, float ts, float tw,
+                                                bool boundary, bool use_m, const DnGroup& g) {
+  float gj = ts - tw;
+  de += gj;
+  if (boundary) {
+    mm = g.beta * mm + de / g.Nf;
+    th = th - g.lr * (g.cb_boundary * mm + gj / g.Nf);
+    de = 0.0f;
+  } else if (use_m) {
+    th = th - g.lr * (g.c_beta * mm + gj / g.Nf);
+  } else {
+    th = th - g.lr * (gj / g.Nf);
+  }
+}
+
+template <int VEC>
+__global__ __launch_bounds__(256) void dn_group_kernel(float* theta, float* m, float* delta,
+                                                       DnGroup g, int64_t nvec, int64_t base) {
+  typedef typename Vec<VEC>::T V;
+  const bool use_m = g.c_beta != 0.0f;
+  const bool touch_m = use_m || g.boundary_mask != 0u;
+  int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += stride) {
+    V thv = reinterpret_cast<V*>(theta + base)[i];
+    V dev = reinterpret_cast<V*>(delta + base)[i];
+    V mv;
+    float* th = reinterpret_cast<float*>(&thv);
+    float* de = reinterpret_cast<float*>(&dev);
+    float* mm = reinterpret_cast<float*>(&mv);
+    if (touch_m) mv = reinterpret_cast<V*>(m + base)[i];
+    else
+      for (int e = 0; e < VEC; e++) mm[e] = 0.0f;
+    for (int j = 0; j < g.G; j++) {
+      V tsv = reinterpret_cast<const V*>(g.theta_start[j] + base)[i];
+      V twv = reinterpret_cast<const V*>(g.theta_worker[j] + base)[i];
+      const float* ts = reinterpret_cast<const float*>(&tsv);
+      const float* tw = reinterpret_cast<const float*>(&twv);
+      bool boundary = (g.boundary_mask >> j) & 1u;
+#pragma unroll
+      for (int e = 0; e < VEC; e++) dn_event_scalar(th[e], mm[e], de[e], ts[e], tw[e], boundary, use_m, g);
+    }
+    reinterpret_cast<V*>(theta + base)[i] = thv;
+    reinterpret_cast<V*>(delta + base)[i] = dev;
+    if (g.boundary_mask != 0u) reinterpret_cast<V*>(m + base)[i] = mv;
+    if (g.restart) {
+      for (int j = 0; j < g.G; j++) {
+        reinterpret_cast<V*>(g.theta_worker[j] + base)[i] = thv;
+        reinterpret_cast<V*>(g.start_out[j] + base)[i] = thv;
+        if (g.lp_out[j]) {
+          bf16* lp = g.lp_out[j] + base + (int64_t)VEC * i;
+          if (VEC == 4) store_bf16x4(lp, *reinterpret_cast<float4*>(&thv));
+          else lp[0] = (bf16)th[0];
+        }
+      }
+    }
+  }
+}
+
+int dn_group(float* theta, float* m, float* delta, const DnGroup& g, int64_t P, hipStream_t st) {
+  if (g.G < 1 || g.G > ALS_DN_MAX_GROUP) return set_error(ALS_ERR_INVALID, "dn_group: G out of range");
+  if (P <= 0) return ALS_OK;
+  int64_t n4 = P / 4;
+  if (n4 > 0) {
+    int blocks = blocks_for(n4, 256, 256 * 16);
+    hipLaunchKernelGGL(dn_group_kernel<4>, dim3(blocks), dim3(256), 0, st, theta, m, delta, g, n4,
+                       (int64_t)0);
+    ALS_CHECK_LAUNCH();
+  }
+  if (n4 * 4 < P) {
+    hipLaunchKernelGGL(dn_group_kernel<1>, dim3(1), dim3(64), 0, st, theta, m, delta, g,
+                       P - n4 * 4, n4 * 4);
+    ALS_CHECK_LAUNCH();
+  }
+  return ALS_OK;
+}
+
+// theta -> worker master, round-start snapshot and bf16 working copy (read 4, write up to 10).
+__global__ __launch_bounds__(256) void restart_kernel(const float* __restrict__ theta,
+                                                      float* __restrict__ master,
+                                                      float* __restrict__ start,
+                                                      bf16* __restrict__ lp, int64_t P) {
+  int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  int64_t n4 = P / 4;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+    float4 t = reinterpret_cast<const float4*>(theta)[i];
+    if (master) reinterpret_cast<float4*>(master)[i] = t;
+    if (start) reinterpret_cast<float4*>(start)[i] = t;
+    if (lp) store_bf16x4(lp + 4 * i, t);
+  }
+  if (blockIdx.x == 0) {
+    for (int64_t i = n4 * 4 + threadIdx.x; i < P; i += blockDim.x) {
+      float t = theta[i];
+      if (master) master[i] = t;
+      if (start) start[i] = t;
+      if (lp) lp[i] = (bf16)t;
+    }
+  }
+}
+
+int restart_copy(const float* theta, float* master, float* start, bf16* lp, int64_t P,
+                 hipStream_t st) {
+  if (P <= 0) return ALS_OK;
+  int blocks = blocks_for(P / 4 + 1, 256, 256 * 16);
+  hipLaunchKernelGGL(restart_kernel, dim3(blocks), dim3(256), 0, st, theta, master, start, lp, P);
+  ALS_CHECK_LAUNCH();
+  return ALS_OK;
+}
+
+int cast_copy(const float* src, void* dst, int64_t n, int dst_bf16, hipStream_t st) {
+  if (dst_bf16) return restart_copy(src, nullptr, nullptr, (bf16*)dst, n, st);
+  return restart_copy(src, (float*)dst, nullptr, nullptr, n, st);
+}
+
+// ------------------------------------------------------------------------------------------
+// Embedding: x[b*S+s,:] = E[tok[b,s],:] + Ppos[s,:]   (tokens are [B,S+1]; inputs are s < S)
+// ------------------------------------------------------------------------------------------
+__global__ void embed_fwd_kernel(const int32_t* __restrict__ tok, const float* __restrict__ E,
+                                 const float* __restrict__ Ppos, float* __restrict__ x, int S,
+                                 int d, int V) {
+  int t = blockIdx.x;
+  int b = t / S, s = t % S;
+  int id = tok[(int64_t)b * (S + 1) + s];
+  id = id < 0 ? 0 : (id >= V ? V - 1 : id);  // out-of-range ids are clamped, never dereferenced
+  const float4* e = reinterpret_cast<const float4*>(E + (int64_t)id * d);
+  const float4* p = reinterpret_cast<const float4*>(Ppos + (int64_t)s * d);
+  float4* o = reinterpret_cast<float4*>(x + (int64_t)t * d);
+  for (int c = threadIdx.x; c < d / 4; c += blockDim.x) {
+    float4 a = e[c], q = p[c];
+    o[c] = make_float4(a.x + q.x, a.y + q.y, a.z + q.z, a.w + q.w);
+  }
+}
+
+int embed_fwd(const int32_t* tok, const float* E, const float* Ppos, float* x, int B, int S, int d,
+              int V, hipStream_t st) {
+  int threads = d / 4 < 256 ? (d / 4 < 64 ? 64 : d / 4) : 256;
+  hipLaunchKernelGGL(embed_fwd_kernel, dim3(B * S), dim3(threads), 0, st, tok, E, Ppos, x, S, d, V);
+  ALS_CHECK_LAUNCH();
+  return ALS_OK;
+}
+
+// Embedding gradient without float atomics, so that a step is bit-reproducible.
+// (1) embed_sort: one workgroup per step orders the T input positions by token id with a
+//     counting sort whose ranks are fixed by position order: offset[v] .. offset[v+1] delimit
+//     the positions holding token v inside pos[].  It depends on the tokens only, so one
+//     launch prepares every step of a local round.
+// (2) embed_bwd_rows: one workgroup per vocabulary row adds the dx rows of its positions
+//     (wave w takes every 4th position, the four partial rows are added in a fixed order)
+//     and writes the row, zeros included.
+// dPpos[s,:] = sum_b dx[b,s,:] in batch order.
+__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    int n = __shfl_up(v, o, 64);
+    if (lane >= o) v += n;
+  }
+  return v;
+}
+
+__global__ __launch_bounds__(1024) void embed_sort_kernel(const int32_t* __restrict__ tok, int B,
+                                                          int S, int V, int32_t* offset,
+                                                          int32_t* rank, int32_t* pos) {
+  __shared__ int ids[1024];
+  __shared__ int wsum[16];
+  __shared__ int carry_s;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int T = B * S;
+  const int32_t* tk = tok + (int64_t)blockIdx.x * B * (S + 1);
+  int32_t* cnt = offset + (int64_t)blockIdx.x * (V + 1);
+  int32_t* rk = rank + (int64_t)blockIdx.x * T;
+  int32_t* ps = pos + (int64_t)blockIdx.x * T;
+  for (int v = tid; v <= V; v += 1024) cnt[v] = 0;
+  __syncthreads();
+  for (int c0 = 0; c0 < T; c0 += 1024) {
+    int t = c0 + tid;
+    bool active = t < T;
+    int id = active ? tk[(int64_t)(t / S) * (S + 1) + (t % S)] : -1;
+    if (active) id = id < 0 ? 0 : (id >= V ? V - 1 : id);
+    ids[tid] = id;
+    __syncthreads();
+    int before = 0, after = 0;
+    int n = T - c0 < 1024 ? T - c0 : 1024;
+    if (active)
+      for (int j = 0; j < n; j++) {
+        int eq = ids[j] == id;
+        before += eq & (j < tid);
+        after += eq & (j > tid);
+      }
+    int base = active ? cnt[id] : 0;
+    if (active) rk[t] = base + before;
+    __syncthreads();
+    if (active && after == 0) cnt[id] = base + before + 1;
+    __syncthreads();
+  }
+  // exclusive prefix sum of cnt[0..V] in place
+  if (tid == 0) carry_s = 0;
+  __syncthreads();
+  for (int v0 = 0; v0 <= V; v0 += 1024) {
+    int v = v0 + tid;
+    int x = v <= V ? cnt[v] : 0;
+    int incl = wave_incl_scan(x, lane);
+    if (lane == 63) wsum[wv] = incl;
+    __syncthreads();
+    int add = carry_s;
+    for (int w = 0; w < wv; w++) add += wsum[w];
+    if (v <= V) cnt[v] = incl - x + add;
+    __syncthreads();
+    if (tid == 1023) carry_s = add + incl;
+    __syncthreads();
+  }
+  for (int t = tid; t < T; t += 1024) {
+    int id = tk[(int64_t)(t / S) * (S + 1) + (t % S)];
+    id = id < 0 ? 0 : (id >= V ? V - 1 : id);
+    ps[cnt[id] + rk[t]] = t;
+  }
+}
+
+int embed_sort(const int32_t* tok, int n_steps, int B, int S, int V, int32_t* offset, int32_t* rank,
+               int32_t* pos, hipStream_t st) {
+  if (n_steps <= 0) return ALS_OK;
+  hipLaunchKernelGGL(embed_sort_kernel, dim3(n_steps), dim3(1024), 0, st, tok, B, S, V, offset, rank, pos);
+  ALS_CHECK_LAUNCH();
+  return ALS_OK;
+}
+
+#define EMB_MAXD4 4  // float4 slots per lane: d <= 1024
+__global__ __launch_bounds__(256) void embed_bwd_rows_kernel(const int32_t* __restrict__ offset,
+                                                             const int32_t* __restrict__ pos,
+                                                             const float* __restrict__ dx,
+                                                             float* __restrict__ dE, int d) {
+  extern __shared__ float smem[];  // [4][d]
+  const int v = blockIdx.x, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int beg = offset[v], end = offset[v + 1];
+  const int d4 = d / 4;
+  float4* out = reinterpret_cast<float4*>(dE + (int64_t)v * d);
+  if (beg == end) {
+    for (int c = threadIdx.x; c < d4; c += 256) out[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+    return;
+  }
+  float4 acc[EMB_MAXD4];
+#pragma unroll
+  for (int s = 0; s < EMB_MAXD4; s++) acc[s] = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int r = beg + w; r < end; r += 4) {
+    const float4* row = reinterpret_cast<const float4*>(dx + (int64_t)pos[r] * d);
+#pragma unroll
+    for (int s = 0; s < EMB_MAXD4; s++) {
+      int c = lane + 64 * s;
+      if (c < d4) {
+        float4 x = row[c];
+        acc[s].x += x.x; acc[s].y += x.y; acc[s].z += x.z; acc[s].w += x.w;
+      }
+    }
+  }
+#pragma unroll
+  for (int s = 0; s < EMB_MAXD4; s++) {
+    int c = lane + 64 * s;
+    if (c < d4) reinterpret_cast<float4*>(smem + w * d)[c] = acc[s];
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < d; c += 256)
+    dE[(int64_t)v * d + c] = ((smem[c] + smem[d + c]) + smem[2 * d + c]) + smem[3 * d + c];
+}
+
+__global__ void embed_bwd_pos_kernel(const float* __restrict__ dx, float* __restrict__ dPpos,
+                                     int B, int S, int d) {
+  int s = blockIdx.x;
+  for (int c = threadIdx.x; c < d; c += blockDim.x) {
+    float acc = 0.0f;
+    for (int b = 0; b < B; b++) acc += dx[((int64_t)b * S + s) * d + c];
+    dPpos[(int64_t)s * d + c] = acc;
+  }
+}
+
+int embed_bwd(const int32_t* offset, const int32_t* pos, const float* dx, float* dE, float* dPpos,
+              int B, int S, int d, int V, hipStream_t st) {
+  if (d > 256 * EMB_MAXD4 || d % 4) return set_error(ALS_ERR_INVALID, "embed_bwd: d unsupported");
+  hipLaunchKernelGGL(embed_bwd_rows_kernel, dim3(V), dim3(256), (size_t)4 * d * sizeof(float), st, offset,
+                     pos, dx, dE, d);
+  ALS_CHECK_LAUNCH();
+  int threads = d < 256 ? d : 256;
+  hipLaunchKernelGGL(embed_bwd_pos_kernel, dim3(S), dim3(threads), 0, st, dx, dPpos, B, S, d);
+  ALS_CHECK_LAUNCH();
+  return ALS_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// RMSNorm: y = x * rsqrt(mean(x^2) + eps) * g ; one 64-lane wavefront per row.
+// ------------------------------------------------------------------------------------------
+template <typename OT>
+__global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const float* __restrict__ x,
+                                                          const float* __restrict__ g,
+                                                          OT* __restrict__ y,
+                                                          float* __restrict__ rstd, int T, int d,
+                                                          float eps) {
+  int lane = threadIdx.x & 63;
+  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= T) return;
+  const float4* xr = reinterpret_cast<const float4*>(x + (int64_t)row * d);
+  const float4* g4 = reinterpret_cast<const float4*>(g);
+  float ss = 0.0f;
+  for (int c = lane; c < d / 4; c += 64) {
+    float4 v = xr[c];
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  ss = wave_sum(ss);
+  float r = 1.0f / sqrtf(ss / (float)d + eps);
+  if (lane == 0) rstd[row] = r;
+  OT* yr = y + (int64_t)row * d;
+  for (int c = lane; c < d / 4; c += 64) {
+    float4 v = xr[c], gg = g4[c];
+    float4 o = make_float4(v.x * r * gg.x, v.y * r * gg.y, v.z * r * gg.z, v.w * r * gg.w);
+    if (sizeof(OT) == 2) store_bf16x4(reinterpret_cast<bf16*>(yr) + 4 * c, o);
+    else reinterpret_cast<float4*>(yr)[c] = o;
+  }
+}
+
+int rmsnorm_fwd(const float* x, const float* g, void* y, float* rstd, int T, int d, float eps,
+                int out_bf16, hipStream_t st) {
+  dim3 grid((T + 3) / 4), block(256);
+  if (out_bf16)
+    hipLaunchKernelGGL(rmsnorm_fwd_kernel<bf16>, grid, block, 0, st, x, g, (bf16*)y, rstd, T, d, eps);
+  else
+    hipLaunchKernelGGL(rmsnorm_fwd_kernel<float>, grid, block, 0, st, x, g, (float*)y, rstd, T, d, eps);
+  ALS_CHECK_LAUNCH();
+  return ALS_OK;
+}
+
+// Backward: xhat = x rstd ; dxhat = dy g ; dx = rstd (dxhat - xhat mean(dxhat xhat)) ;
+// dg = sum_rows dy xhat.  Each block walks rows with a fixed stride and leaves one partial dg
+// row; a second kernel adds the partials in a fixed order.
+#define RMS_BWD_MAXD4 4  // per-lane float4 slots: supports d <= 1024
+template <typename LT>
+__global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(
+    const float* __restrict__ dy, const float* __restrict__ x, const float* __restrict__ rstd,
+    const float* __restrict__ g, const float* dx_in, float* dx_out, LT* __restrict__ dx_lp,
+    float* __restrict__ partial, int T, int d) {
+  extern __shared__ float smem[];  // [4][d]
+  int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  int d4 = d / 4;
+  float4 dg[RMS_BWD_MAXD4];
+#pragma unroll
+  for (int s = 0; s < RMS_BWD_MAXD4; s++) dg[s] = make_float4(0.f, 0.f, 0.f, 0.f);
+  const float4* g4 = reinterpret_cast<const float4*>(g);
+  for (int row = blockIdx.x * 4 + w; row < T; row += gridDim.x * 4) {
+    const float4* xr = reinterpret_cast<const float4*>(x + (int64_t)row * d);
+    const float4* dyr = reinterpret_cast<const float4*>(dy + (int64_t)row * d);
+    float r = rstd[row];
+    float dot = 0.0f;
+#pragma unroll
+    for (int s = 0; s < RMS_BWD_MAXD4; s++) {
+      int c = lane + 64 * s;
+      if (c < d4) {
+        float4 xv = xr[c], dv = dyr[c], gg = g4[c];
+        dot += dv.x * gg.x * xv.x * r + dv.y * gg.y * xv.y * r + dv.z * gg.z * xv.z * r +
+               dv.w * gg.w * xv.w * r;
+      }
+    }
+    dot = wave_sum(dot) / (float)d;
+#pragma unroll
+    for (int s = 0; s < RMS_BWD_MAXD4; s++) {
+      int c = lane + 64 * s;
+      if (c < d4) {
+        float4 xv = xr[c], dv = dyr[c], gg = g4[c];
+        float4 xh = make_float4(xv.x * r, xv.y * r, xv.z * r, xv.w * r);
+        dg[s].x += dv.x * xh.x; dg[s].y += dv.y * xh.y; dg[s].z += dv.z * xh.z; dg[s].w += dv.w * xh.w;
+        float4 o = make_float4(r * (dv.x * gg.x - xh.x * dot), r * (dv.y * gg.y - xh.y * dot),
+                               r * (dv.z * gg.z - xh.z * dot), r * (dv.w * gg.w - xh.w * dot));
+        if (dx_in) {
+          float4 a = reinterpret_cast<const float4*>(dx_in + (int64_t)row * d)[c];
+          o.x += a.x; o.y += a.y; o.z += a.z; o.w += a.w;
+        }
+        reinterpret_cast<float4*>(dx_out + (int64_t)row * d)[c] = o;
+        if (dx_lp) {
+          if (sizeof(LT) == 2) store_bf16x4(reinterpret_cast<bf16*>(dx_lp) + (int64_t)row * d + 4 * c, o);
+          else reinterpret_cast<float4*>(reinterpret_cast<float*>(dx_lp) + (int64_t)row * d)[c] = o;
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int s = 0; s < RMS_BWD_MAXD4; s++) {
+    int c = lane + 64 * s;
+    if (c < d4) reinterpret_cast<float4*>(smem + w * d)[c] = dg[s];
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < d; c += 256)
+    partial[(int64_t)blockIdx.x * d + c] = smem[c] + smem[d + c] + smem[2 * d + c] + smem[3 * d + c];
+}
+
+__global__ void sum_partials_kernel(const float* __restrict__ partial, float* __restrict__ out,
+                                    int nblk, int d) {
+  int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= d) return;
+  float acc = 0.0f;
+  for (int b = 0; b < nblk; b++) acc += partial[(int64_t)b * d + c];
+  out[c] = acc;
+}
+
+int rmsnorm_bwd_blocks(int T) {
+  int b = (T + 3) / 4;
+  return b > 512 ? 512 : b;
+}
+
+int rmsnorm_bwd(const float* dy, const float* x, const float* rstd, const float* g,
+                const float* dx_in, float* dx_out, void* dx_lp, int lp_bf16, float* dg,
+                float* partial, int T, int d, hipStream_t st) {
+  if (d > 256 * RMS_BWD_MAXD4 || d % 4) return set_error(ALS_ERR_INVALID, "rmsnorm_bwd: d unsupported");
+  int nblk = rmsnorm_bwd_blocks(T);
+  size_t sm = (size_t)4 * d * sizeof(float);
+  if (lp_bf16)
+    hipLaunchKernelGGL(rmsnorm_bwd_kernel<bf16>, dim3(nblk), dim3(256), sm, st, dy, x, rstd, g, dx_in,
+                       dx_out, (bf16*)dx_lp, partial, T, d);
+  else
+    hipLaunchKernelGGL(rmsnorm_bwd_kernel<float>, dim3(nblk), dim3(256), sm, st, dy, x, rstd, g, dx_in,
+                       dx_out, (float*)dx_lp, partial, T, d);
+  ALS_CHECK_LAUNCH();
+  hipLaunchKernelGGL(sum_partials_kernel, dim3((d + 63) / 64), dim3(64), 0, st, partial, dg, nblk, d);
+  ALS_CHECK_LAUNCH();
+  return ALS_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Softmax cross-entropy on fp32 logits, one block per row: loss_row = logsumexp - logit[target];
+// dlogits = (softmax - onehot) / T.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ float block_reduce(float v, bool is_max, float* sh) {
+  int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  v = is_max ? wave_max(v) : wave_sum(v);
+  __syncthreads();
+  if (lane == 0) sh[w] = v;
+  __syncthreads();
+  int nw = blockDim.x >> 6;
+  float r = sh[0];
+  for (int i = 1; i < nw; i++) r = is_max ? fmaxf(r, sh[i]) : r + sh[i];
+  return r;
+}
+
+template <typename OT>
+__global__ __launch_bounds__(256) void cross_entropy_kernel(const float* __restrict__ logits,
+                                                            const int32_t* __restrict__ tok,
+                                                            float* __restrict__ loss_row,
+                                                            OT* __restrict__ dl, int S, int V,
+                                                            float invT) {
+  __shared__ float sh[8];
+  int t = blockIdx.x;
+  int b = t / S, s = t % S;
+  int tgt = tok[(int64_t)b * (S + 1) + s + 1];
+  tgt = tgt < 0 ? 0 : (tgt >= V ? V - 1 : tgt);
+  const float* lr = logits + (int64_t)t * V;
+  float mx = -INFINITY;
+  for (int c = threadIdx.x; c < V; c += blockDim.x) mx = fmaxf(mx, lr[c]);
+  mx = block_reduce(mx, true, sh);
+  float sum = 0.0f;
+  for (int c = threadIdx.x; c < V; c += blockDim.x) sum += expf(lr[c] - mx);
+  sum = block_reduce(sum, false, sh);
+  float lse = mx + logf(sum);
+  if (threadIdx.x == 0) loss_row[t] = lse - lr[tgt];
+  OT* dr = dl + (int64_t)t * V;
+  for (int c = threadIdx.x; c < V; c += blockDim.x) {
+    float p = expf(lr[c] - lse);
+    if (c == tgt) p -= 1.0f;
+    dr[c] = (OT)(p * invT);
+  }
+}
+
+int cross_entropy(const float* logits, const int32_t* tok, float* loss_row, void* dlogits,
+                  int dl_bf16, int B, int S, int V, hipStream_t st) {
+  int T = B * S;
+  float invT = 1.0f / (float)T;
+  if (dl_bf16)
+    hipLaunchKernelGGL(cross_entropy_kernel<bf16>, dim3(T), dim3(256), 0, st, logits, tok, loss_row,
+                       (bf16*)dlogits, S, V, invT);
+  else
+    hipLaunchKernelGGL(cross_entropy_kernel<float>, dim3(T), dim3(256), 0, st, logits, tok, loss_row,
+                       (float*)dlogits, S, V, invT);
+  ALS_CHECK_LAUNCH();
+  return ALS_OK;
+}
+
+__global__ __launch_bounds__(1024) void mean_rows_kernel(const float* __restrict__ v,
+                                                         float* __restrict__ out, int T) {
+  __shared__ float sh[16];
+  float acc = 0.0f;
+  for (int i = threadIdx.x; i < T; i += blockDim.x) acc += v[i];
+  acc = block_reduce(acc, false, sh);
+  if (threadIdx.x == 0) out[0] = acc / (float)T;
+}
+
+int mean_rows(const float* loss_row, float* out, int T, hipStream_t st) {
+  hipLaunchKernelGGL(mean_rows_kernel, dim3(1), dim3(1024), 0, st, loss_row, out, T);
+  ALS_CHECK_LAUNCH();
+  return ALS_OK;
+}
+
+}  // namespace als

@@ -1,0 +1,314 @@
+// bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate) for the
+// worker step's projections: C[M,N] = sum_k A(m,k) B(k,n).
+//
+// One workgroup of 4 wavefronts (2 x 2) owns a BM x BN tile of C and walks K in slices of 64,
+// double-buffered through LDS; each wavefront owns a (BM/2) x (BN/2) sub-tile made of 32 x 32
+// MFMA blocks.  Operands may be stored with the contraction index contiguous (read from LDS
+// with 16-byte loads, rows padded by 16 bytes so that 8 neighbouring rows hit different banks)
+// or with the contraction index strided (read with the LDS transpose load ds_read_b64_tr_b16,
+// rows padded by 32 bytes), so forward (x W), input-gradient (dY W^T) and weight-gradient
+// (X^T dY) products all read the tensors as they lie in memory, without transposed copies.
+// Weight-gradient products have small M x N and very long K: they are split along K over
+// grid.z into fp32 partials that a second kernel adds in a fixed order.
+//
+// Lane layouts of the MFMA (wavefront lane l, 64 lanes):
+//   A fragment: row l%32, k = 8*(l/32) .. +7 ; B fragment: column l%32, same k ;
+//   accumulator element v (0..15): row 8*(v/4) + 4*(l/32) + v%4, column l%32.
+// LDS transpose load: in each group of 16 lanes, lane s supplies 4 consecutive bf16; lane r
+// receives element r%4 of lanes r/4, 4 + r/4, 8 + r/4, 12 + r/4.
+#include "common.h"
+
+namespace als {
+
+namespace {
+
+constexpr int BK = 64;
+
+template <int BM, int BN, int AL, int BL>
+struct Tile {
+  // AL == 0: A tile kept as [BM rows][64 k] ; AL == 1: as [64 k][BM rows]
+  static constexpr int A_STRIDE = AL == 0 ? BK * 2 + 16 : BM * 2 + 32;
+  static constexpr int A_BYTES = A_STRIDE * (AL == 0 ? BM : BK);
+  // BL == 1: B tile kept as [BN cols][64 k] ; BL == 0: as [64 k][BN cols]
+  static constexpr int B_STRIDE = BL == 1 ? BK * 2 + 16 : BN * 2 + 32;
+  static constexpr int B_BYTES = B_STRIDE * (BL == 1 ? BN : BK);
+  static constexpr int STAGE = A_BYTES + B_BYTES;
+  static constexpr int LDS_BYTES = 2 * STAGE;
+  static constexpr int A_CHUNKS = BM * BK * 2 / 16 / 256;  // 16-byte chunks per thread
+  static constexpr int B_CHUNKS = BN * BK * 2 / 16 / 256;
+};
+
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+__device__ __forceinline__ bf16x8 lds_read_direct(const char* p) {
+  return *reinterpret_cast<const bf16x8*>(p);
+}
+
+// two transpose loads: k rows kb..kb+3 and kb+4..kb+7 of a [k][row] tile
+__device__ __forceinline__ bf16x8 lds_read_tr(const char* p, int stride) {
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * stride));
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  s16x8 r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+__device__ __forceinline__ float gelu_f(float u) {
+  const float a = 0.7978845608028654f, b = 0.044715f;
+  return 0.5f * u * (1.0f + tanhf(a * (u + b * u * u * u)));
+}
+__device__ __forceinline__ float gelu_grad_f(float u) {
+  const float a = 0.7978845608028654f, b = 0.044715f;
+  float th = tanhf(a * (u + b * u * u * u));
+  return 0.5f * (1.0f + th) + 0.5f * u * (1.0f - th * th) * a * (1.0f + 3.0f * b * u * u);
+}
+
+struct MfmaArgs {
+  const bf16* A; const bf16* B;
+  int64_t lda, ldb;
+  int M, N, K;      // K = length of this launch's K range per split
+  int tiles_m, tiles_n;
+  void* C; int64_t ldc;
+  const float* R; int64_t ldr;
+  void* C2; const bf16* U;
+  int64_t split_stride;  // elements between split partials (split-K only)
+};
+
+template <int BM, int BN, int AL, int BL, int EPI, typename TO, bool SPLIT>
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(MfmaArgs g) {
+  typedef Tile<BM, BN, AL, BL> TL;
+  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  // Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of
+  // tiles (n fastest) so that tiles sharing an A panel share an L2.
+  int ntiles = g.tiles_m * g.tiles_n;
+  int id = blockIdx.x;
+  int per = ntiles / 8;
+  int tile = (id < per * 8) ? (id % 8) * per + id / 8 : id;
+  const int m0 = (tile / g.tiles_n) * BM, n0 = (tile % g.tiles_n) * BN;
+  const int64_t kbase = (int64_t)blockIdx.z * g.K;
+
+  const bf16* Ag = AL == 0 ? g.A + (int64_t)m0 * g.lda + kbase : g.A + kbase * g.lda + m0;
+  const bf16* Bg = BL == 1 ? g.B + (int64_t)n0 * g.ldb + kbase : g.B + kbase * g.ldb + n0;
+
+  uint4 ra[TL::A_CHUNKS], rb[TL::B_CHUNKS];
+
+  auto load_global = [&](int kt) {
+#pragma unroll
+    for (int i = 0; i < TL::A_CHUNKS; i++) {
+      int c = tid + i * 256;
+      const bf16* p;
+      if (AL == 0) p = Ag + (int64_t)(c >> 3) * g.lda + kt * BK + (c & 7) * 8;
+      else p = Ag + (int64_t)(kt * BK + c / (BM / 8)) * g.lda + (c % (BM / 8)) * 8;
+      ra[i] = *reinterpret_cast<const uint4*>(p);
+    }
+#pragma unroll
+    for (int i = 0; i < TL::B_CHUNKS; i++) {
+      int c = tid + i * 256;
+      const bf16* p;
+      if (BL == 1) p = Bg + (int64_t)(c >> 3) * g.ldb + kt * BK + (c & 7) * 8;
+      else p = Bg + (int64_t)(kt * BK + c / (BN / 8)) * g.ldb + (c % (BN / 8)) * 8;
+      rb[i] = *reinterpret_cast<const uint4*>(p);
+    }
+  };
+  auto store_lds = [&](int buf) {
+    char* As = smem + buf * TL::STAGE;
+    char* Bs = As + TL::A_BYTES;
+#pragma unroll
+    for (int i = 0; i < TL::A_CHUNKS; i++) {
+      int c = tid + i * 256;
+      int off = AL == 0 ? (c >> 3) * TL::A_STRIDE + (c & 7) * 16
+                        : (c / (BM / 8)) * TL::A_STRIDE + (c % (BM / 8)) * 16;
+      *reinterpret_cast<uint4*>(As + off) = ra[i];
+    }
+#pragma unroll
+    for (int i = 0; i < TL::B_CHUNKS; i++) {
+      int c = tid + i * 256;
+      int off = BL == 1 ? (c >> 3) * TL::B_STRIDE + (c & 7) * 16
+                        : (c / (BN / 8)) * TL::B_STRIDE + (c % (BN / 8)) * 16;
+      *reinterpret_cast<uint4*>(Bs + off) = rb[i];
+    }
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) acc[i][j][v] = 0.0f;
+
+  // per-lane fragment offsets inside a stage
+  int a_off, b_off;
+  if (AL == 0) a_off = (wm * WM + (lane & 31)) * TL::A_STRIDE + (lane >> 5) * 16;
+  else a_off = ((lane >> 5) * 8 + ((lane & 15) >> 2)) * TL::A_STRIDE + (wm * WM + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;
+  if (BL == 1) b_off = (wn * WN + (lane & 31)) * TL::B_STRIDE + (lane >> 5) * 16;
+  else b_off = ((lane >> 5) * 8 + ((lane & 15) >> 2)) * TL::B_STRIDE + (wn * WN + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;
+
+  const int nk = g.K / BK;
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+  for (int kt = 0; kt < nk; kt++) {
+    if (kt + 1 < nk) load_global(kt + 1);
+    const char* As = smem + (kt & 1) * TL::STAGE;
+    const char* Bs = As + TL::A_BYTES;
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; kk++) {
+      bf16x8 af[TM], bfr[TN];
+#pragma unroll
+      for (int i = 0; i < TM; i++) {
+        if (AL == 0) af[i] = lds_read_direct(As + a_off + i * 32 * TL::A_STRIDE + kk * 32);
+        else af[i] = lds_read_tr(As + a_off + kk * 16 * TL::A_STRIDE + i * 64, TL::A_STRIDE);
+      }
+#pragma unroll
+      for (int j = 0; j < TN; j++) {
+        if (BL == 1) bfr[j] = lds_read_direct(Bs + b_off + j * 32 * TL::B_STRIDE + kk * 32);
+        else bfr[j] = lds_read_tr(Bs + b_off + kk * 16 * TL::B_STRIDE + j * 64, TL::B_STRIDE);
+      }
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) store_lds((kt + 1) & 1);
+    __syncthreads();
+  }
+
+  // epilogue
+  TO* C = reinterpret_cast<TO*>(g.C);
+  if (SPLIT) C += (int64_t)blockIdx.z * g.split_stride;
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++) {
+      int col = n0 + wn * WN + j * 32 + (lane & 31);
+#pragma unroll
+      for (int v = 0; v < 16; v++) {
+        int row = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        int64_t ci = (int64_t)row * g.ldc + col;
+        float x = acc[i][j][v];
+        if (EPI == EPI_RESID) x += g.R[(int64_t)row * g.ldr + col];
+        if (EPI == EPI_DGELU) x *= gelu_grad_f((float)g.U[ci]);
+        C[ci] = (TO)x;
+        if (EPI == EPI_GELU) reinterpret_cast<TO*>(g.C2)[ci] = (TO)gelu_f(x);
+      }
+    }
+}
+
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part,
+                                                            float* __restrict__ C, int64_t n4,
+                                                            int nsplit, int64_t stride4) {
+  int64_t step = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += step) {
+    float4 a = reinterpret_cast<const float4*>(part)[i];
+    for (int s = 1; s < nsplit; s++) {
+      float4 b = reinterpret_cast<const float4*>(part)[i + s * stride4];
+      a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    }
+    reinterpret_cast<float4*>(C)[i] = a;
+  }
+}
+
+template <int BM, int BN, int AL, int BL, int EPI, typename TO, bool SPLIT>
+int launch(const MfmaArgs& a, int nsplit, hipStream_t st) {
+  typedef Tile<BM, BN, AL, BL> TL;
+  auto kern = gemm_mfma_kernel<BM, BN, AL, BL, EPI, TO, SPLIT>;
+  static bool attr_set = false;  // idempotent; a race only repeats the call
+  if (!attr_set) {
+    ALS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES));
+    attr_set = true;
+  }
+  dim3 grid(a.tiles_m * a.tiles_n, 1, nsplit);
+  hipLaunchKernelGGL(kern, grid, dim3(256), TL::LDS_BYTES, st, a);
+  ALS_CHECK_LAUNCH();
+  return ALS_OK;
+}
+
+// Tile choice: 256-wide tiles when they divide the shape and still give every CU work.
+inline bool fits(int M, int N, int bm, int bn) { return M % bm == 0 && N % bn == 0; }
+
+}  // namespace
+
+bool gemm_mfma_supported(const GemmDesc& g) {
+  if (!g.in_bf16) return false;
+  if (g.M % 128 || g.N % 128 || g.K % 64 || g.K < 64) return false;
+  if (g.lda % 8 || g.ldb % 8) return false;
+  if ((uintptr_t)g.A % 16 || (uintptr_t)g.B % 16) return false;
+  // operand-layout / epilogue combinations the hot path uses
+  if (g.a_layout == 0 && g.b_layout == 0)
+    return g.epi == EPI_STORE || (g.epi == EPI_RESID && !g.c_bf16) || (g.epi == EPI_GELU && g.c_bf16);
+  if (g.a_layout == 0 && g.b_layout == 1) return g.epi == EPI_STORE || (g.epi == EPI_DGELU && g.c_bf16);
+  if (g.a_layout == 1 && g.b_layout == 0) return g.epi == EPI_STORE && !g.c_bf16;
+  return false;
+}
+
+#define ALS_TILE_SWITCH(AL, BL, EPI, TO, SPLIT)                                                  \
+  do {                                                                                           \
+    if (bm == 256 && bn == 256) return launch<256, 256, AL, BL, EPI, TO, SPLIT>(a, nsplit, st);  \
+    if (bm == 256 && bn == 128) return launch<256, 128, AL, BL, EPI, TO, SPLIT>(a, nsplit, st);  \
+    return launch<128, 128, AL, BL, EPI, TO, SPLIT>(a, nsplit, st);                              \
+  } while (0)
+
+static int dispatch(const GemmDesc& g, const MfmaArgs& a, int bm, int bn, int nsplit, hipStream_t st) {
+  if (g.a_layout == 0 && g.b_layout == 0) {
+    if (g.epi == EPI_RESID) ALS_TILE_SWITCH(0, 0, EPI_RESID, float, false);
+    if (g.epi == EPI_GELU) ALS_TILE_SWITCH(0, 0, EPI_GELU, bf16, false);
+    if (g.c_bf16) ALS_TILE_SWITCH(0, 0, EPI_STORE, bf16, false);
+    ALS_TILE_SWITCH(0, 0, EPI_STORE, float, false);
+  }
+  if (g.a_layout == 0 && g.b_layout == 1) {
+    if (g.epi == EPI_DGELU) ALS_TILE_SWITCH(0, 1, EPI_DGELU, bf16, false);
+    if (g.c_bf16) ALS_TILE_SWITCH(0, 1, EPI_STORE, bf16, false);
+    ALS_TILE_SWITCH(0, 1, EPI_STORE, float, false);
+  }
+  if (nsplit > 1) ALS_TILE_SWITCH(1, 0, EPI_STORE, float, true);
+  ALS_TILE_SWITCH(1, 0, EPI_STORE, float, false);
+}
+
+int gemm_mfma(const GemmDesc& g, hipStream_t st) {
+  if (!gemm_mfma_supported(g)) return set_error(ALS_ERR_INVALID, "gemm_mfma: unsupported shape or layout");
+  int bm = 128, bn = 128;
+  const int target = 256;  // one tile per CU at least
+  if (fits(g.M, g.N, 256, 256) && (g.M / 256) * (g.N / 256) >= target) { bm = 256; bn = 256; }
+  else if (fits(g.M, g.N, 256, 128) && (g.M / 256) * (g.N / 128) >= target) { bm = 256; bn = 128; }
+  MfmaArgs a;
+  a.A = (const bf16*)g.A; a.B = (const bf16*)g.B; a.lda = g.lda; a.ldb = g.ldb;
+  a.M = g.M; a.N = g.N; a.K = g.K; a.tiles_m = g.M / bm; a.tiles_n = g.N / bn;
+  a.C = g.C; a.ldc = g.ldc; a.R = g.R; a.ldr = g.ldr; a.C2 = g.C2; a.U = (const bf16*)g.U;
+  a.split_stride = 0;
+  int nsplit = 1;
+  if (g.a_layout == 1 && g.b_layout == 0 && g.ldc == g.N) {
+    // weight-gradient shape: few tiles, long K.  Split K so the grid covers the chip, as far
+    // as the workspace allows; each split keeps at least 512 of K.
+    int tiles = a.tiles_m * a.tiles_n;
+    int want = (2 * target + tiles - 1) / tiles;
+    int maxk = g.K / 512;
+    size_t per = (size_t)g.M * g.N * sizeof(float);
+    int maxws = g.ws ? (int)(g.ws_bytes / per) : 1;
+    nsplit = want < maxk ? want : maxk;
+    if (nsplit > maxws) nsplit = maxws;
+    if (nsplit < 1) nsplit = 1;
+    while (nsplit > 1 && (g.K % (nsplit * BK))) nsplit--;
+  }
+  if (nsplit > 1) {
+    a.K = g.K / nsplit;
+    a.C = g.ws; a.ldc = g.N; a.split_stride = (int64_t)g.M * g.N;
+    int rc = dispatch(g, a, bm, bn, nsplit, st);
+    if (rc) return rc;
+    int64_t n4 = (int64_t)g.M * g.N / 4;
+    int blocks = (int)((n4 + 255) / 256 < 4096 ? (n4 + 255) / 256 : 4096);
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks), dim3(256), 0, st, g.ws, (float*)g.C, n4,
+                       nsplit, n4);
+    ALS_CHECK_LAUNCH();
+    return ALS_OK;
+  }
+  return dispatch(g, a, bm, bn, 1, st);
+}
+
+}  // namespace als

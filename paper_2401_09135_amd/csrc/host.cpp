@@ -1,0 +1,161 @@
+// Host-only parts of the library: error text, configuration checks, the flat parameter
+// layout, Dynamic Local Updates (Eq. DyLU) and the event order of the asynchronous loop
+// (Alg. 2 with get_worker() from the appendix) on a simulated clock.
+#include "common.h"
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <limits>
+#include <vector>
+
+namespace als {
+
+static thread_local char g_err[512] = "";
+
+int set_error(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int validate_config(const als_config* c) {
+  if (!c) return set_error(ALS_ERR_INVALID, "config is null");
+  if (c->n_layers < 1 || c->n_layers > 64) return set_error(ALS_ERR_INVALID, "n_layers must be in 1..64");
+  if (c->d_model < 64 || c->d_model % 64 || c->d_model > 1024)
+    return set_error(ALS_ERR_INVALID, "d_model must be a multiple of 64 in 64..1024");
+  if (c->n_heads < 1 || c->d_model % c->n_heads) return set_error(ALS_ERR_INVALID, "d_model must be divisible by n_heads");
+  int dh = c->d_model / c->n_heads;
+  if (dh != 32 && dh != 64) return set_error(ALS_ERR_INVALID, "head width d_model/n_heads must be 32 or 64");
+  if (c->d_ff < 64 || c->d_ff % 64) return set_error(ALS_ERR_INVALID, "d_ff must be a positive multiple of 64");
+  if (c->vocab < 2) return set_error(ALS_ERR_INVALID, "vocab must be >= 2");
+  if (c->seq_len < 1 || c->seq_len > 1024) return set_error(ALS_ERR_INVALID, "seq_len must be in 1..1024");
+  if (c->batch < 1) return set_error(ALS_ERR_INVALID, "batch must be >= 1");
+  if ((int64_t)c->batch * c->seq_len > (1 << 22)) return set_error(ALS_ERR_INVALID, "batch*seq_len too large");
+  if (c->dtype != ALS_DTYPE_F32 && c->dtype != ALS_DTYPE_BF16) return set_error(ALS_ERR_INVALID, "unknown dtype");
+  if (c->n_workers < 1 || c->n_workers > ALS_MAX_WORKERS) return set_error(ALS_ERR_INVALID, "n_workers out of range");
+  if (c->dn_N < 1) return set_error(ALS_ERR_INVALID, "dn_N must be >= 1");
+  if (c->max_local_steps < 1) return set_error(ALS_ERR_INVALID, "max_local_steps must be >= 1");
+  if (!(c->adam_beta1 >= 0 && c->adam_beta1 < 1) || !(c->adam_beta2 >= 0 && c->adam_beta2 < 1) ||
+      !(c->adam_eps > 0) || !(c->weight_decay >= 0))
+    return set_error(ALS_ERR_INVALID, "AdamW hyper-parameters out of range");
+  if (!(c->outer_beta >= 0 && c->outer_beta < 1) || !isfinite(c->outer_lr))
+    return set_error(ALS_ERR_INVALID, "outer optimiser hyper-parameters out of range");
+  // momentum activation c of Alg. 3 lies in [0, 1/N]
+  if (!(c->dn_c >= 0 && c->dn_c <= 1.0 / c->dn_N + 1e-12))
+    return set_error(ALS_ERR_INVALID, "dn_c must lie in [0, 1/N]");
+  if (!(c->norm_eps > 0)) return set_error(ALS_ERR_INVALID, "norm_eps must be > 0");
+  return ALS_OK;
+}
+
+void make_layout(const als_config& c, Layout* L) {
+  int64_t d = c.d_model, ff = c.d_ff, V = c.vocab, S = c.seq_len, off = 0;
+  L->E = off; off += V * d;
+  L->Ppos = off; off += S * d;
+  for (int l = 0; l < c.n_layers; l++) {
+    L->Wqkv[l] = off; off += d * 3 * d;
+    L->Wo[l] = off; off += d * d;
+    L->W1[l] = off; off += d * ff;
+    L->W2[l] = off; off += ff * d;
+  }
+  L->Wout = off; off += d * V;
+  L->P_decay = off;
+  for (int l = 0; l < c.n_layers; l++) {
+    L->g1[l] = off; off += d;
+    L->g2[l] = off; off += d;
+  }
+  L->gf = off; off += d;
+  L->P = off;
+}
+
+}  // namespace als
+
+using namespace als;
+
+extern "C" const char* als_last_error(void) { return g_err; }
+
+extern "C" int64_t als_param_count(const als_config* cfg) {
+  if (validate_config(cfg)) return 0;
+  Layout L; make_layout(*cfg, &L);
+  return L.P;
+}
+extern "C" int64_t als_param_count_decayed(const als_config* cfg) {
+  if (validate_config(cfg)) return 0;
+  Layout L; make_layout(*cfg, &L);
+  return L.P_decay;
+}
+extern "C" int als_param_offsets(const als_config* cfg, int64_t* out, int n_out) {
+  int rc = validate_config(cfg);
+  if (rc) return rc;
+  int n = 6 * cfg->n_layers + 4;
+  if (!out || n_out < n) return set_error(ALS_ERR_INVALID, "offsets_out needs room for %d entries", n);
+  Layout L; make_layout(*cfg, &L);
+  int i = 0;
+  out[i++] = L.E; out[i++] = L.Ppos;
+  for (int l = 0; l < cfg->n_layers; l++) { out[i++] = L.Wqkv[l]; out[i++] = L.Wo[l]; out[i++] = L.W1[l]; out[i++] = L.W2[l]; }
+  out[i++] = L.Wout;
+  for (int l = 0; l < cfg->n_layers; l++) { out[i++] = L.g1[l]; out[i++] = L.g2[l]; }
+  out[i++] = L.gf;
+  return n;
+}
+
+// Eq. (DyLU) in fp64: divide, multiply, floor; a zero count is raised to one step.
+// Event loop: Alg. 2.  A running worker's completion time is start + H_i / v_i; the earliest
+// (time, index) candidate is synchronised when no grace window is open or it falls inside the
+// open one; otherwise every synchronised worker restarts at tau_sync + tau_grace.
+extern "C" int als_dylu_schedule(const double* speeds, int k, int H_max, double tau_grace,
+                                 int n_events, int32_t* H_out, int32_t* ev_worker, double* ev_time,
+                                 int32_t* ev_group_end) {
+  if (!speeds || !H_out) return set_error(ALS_ERR_INVALID, "speeds and H_out must be non-null");
+  if (k <= 0 || k > ALS_MAX_WORKERS) return set_error(ALS_ERR_INVALID, "k out of range");
+  if (H_max < 1) return set_error(ALS_ERR_INVALID, "H_max must be >= 1");
+  if (!(tau_grace >= 0) || !isfinite(tau_grace)) return set_error(ALS_ERR_INVALID, "tau_grace must be finite and >= 0");
+  if (n_events < 0) return set_error(ALS_ERR_INVALID, "n_events must be >= 0");
+  double vmax = 0;
+  for (int i = 0; i < k; i++) {
+    if (!isfinite(speeds[i]) || !(speeds[i] > 0)) return set_error(ALS_ERR_INVALID, "speed %d is not finite and positive", i);
+    if (speeds[i] > vmax) vmax = speeds[i];
+  }
+  for (int i = 0; i < k; i++) {
+    double r = speeds[i] / vmax;
+    int hi = (int)floor(r * (double)H_max);
+    H_out[i] = hi < 1 ? 1 : hi;
+  }
+  if (!ev_worker || n_events == 0) return ALS_OK;
+
+  const double inf = std::numeric_limits<double>::infinity();
+  std::vector<double> done(k);
+  std::vector<char> running(k, 1);
+  std::vector<int> completed;
+  for (int i = 0; i < k; i++) done[i] = 0.0 + (double)H_out[i] / speeds[i];
+  double tau_sync = inf;
+  int emitted = 0;
+  for (;;) {
+    int e = -1;
+    for (int i = 0; i < k; i++)
+      if (running[i] && (e < 0 || done[i] < done[e])) e = i;  // ties keep the smaller index
+    bool take = e >= 0 && (tau_sync == inf || done[e] - tau_sync <= tau_grace);
+    if (take) {
+      if (emitted == n_events) break;  // the open group is cut short: its last flag stays 0
+      if (done[e] < tau_sync) tau_sync = done[e];
+      ev_worker[emitted] = e;
+      if (ev_time) ev_time[emitted] = done[e];
+      if (ev_group_end) ev_group_end[emitted] = 0;
+      running[e] = 0;
+      completed.push_back(e);
+      emitted++;
+    } else {
+      double restart = tau_sync + tau_grace;
+      if (ev_group_end && emitted > 0) ev_group_end[emitted - 1] = 1;
+      for (int i : completed) {
+        done[i] = restart + (double)H_out[i] / speeds[i];
+        running[i] = 1;
+      }
+      completed.clear();
+      tau_sync = inf;
+      if (emitted == n_events) break;
+    }
+  }
+  return ALS_OK;
+}

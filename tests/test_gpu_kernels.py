@@ -1,0 +1,212 @@
+"""GPU parity of the stand-alone kernels against the oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import als_inputs as I
+import paper_2401_09135_amd as A
+from oracle import lm
+from oracle.optim import AdamW, DelayedNesterov
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    return t.to(dtype) if dtype is not None else t
+
+
+def _rel(a, b):
+    return float(np.linalg.norm(a.astype(np.float64) - b.astype(np.float64)) / max(np.linalg.norm(b.astype(np.float64)), 1e-30))
+
+
+@pytest.mark.parametrize("P", [0, 1, 5, 1000, 4 * 256 * 37 + 3, 1 << 20])
+@pytest.mark.parametrize("N,c,G", [(1, 0.0, 1), (4, 0.0, 1), (4, 0.0, 4), (4, 0.1, 3), (3, 0.0, 7), (8, 0.05, 16)])
+def test_dn_group_matches_oracle(P, N, c, G):
+    rng = np.random.default_rng(P + 7 * N + G)
+    f = np.float32
+    theta0 = (rng.standard_normal(P) * 0.02).astype(f)
+    dn = DelayedNesterov(theta0, 0.7, 0.9, N, c)
+    # put the server in a mid-run state: a few events already applied
+    t0 = 2
+    for _ in range(t0):
+        dn.event((rng.standard_normal(P) * 1e-3).astype(f))
+    starts = [(rng.standard_normal(P) * 0.02).astype(f) for _ in range(G)]
+    works = [s + (rng.standard_normal(P) * 1e-3).astype(f) for s in starts]
+    th, m, de = _dev(dn.theta), _dev(dn.m), _dev(dn.delta)
+    ts = [_dev(s) for s in starts]
+    tw = [_dev(w) for w in works]
+    lp = [torch.zeros(max(P, 1), dtype=torch.bfloat16, device=DEV) for _ in range(G)]
+    A.k_dn_group(th, m, de, ts, tw, lp, N, t0, 0.7, 0.9, c, restart=True)
+    torch.cuda.synchronize()
+    for s, w in zip(starts, works):
+        dn.event(s - w)
+    tol = 2e-6
+    if P:
+        assert _rel(th.cpu().numpy(), dn.theta) < tol
+        np.testing.assert_allclose(m.cpu().numpy(), dn.m, rtol=1e-5, atol=1e-9)
+        np.testing.assert_allclose(de.cpu().numpy(), dn.delta, rtol=1e-5, atol=1e-9)
+        for j in range(G):      # restart wrote the new theta everywhere
+            assert torch.equal(ts[j], th) and torch.equal(tw[j], th)
+            assert torch.equal(lp[j][:P], th.to(torch.bfloat16))
+
+
+def test_dn_group_equals_single_events():
+    P, N = 4096 * 3 + 8, 4
+    rng = np.random.default_rng(0)
+    f = np.float32
+    base = [(rng.standard_normal(P) * 0.02).astype(f) for _ in range(3)]
+    starts = [(rng.standard_normal(P) * 0.02).astype(f) for _ in range(5)]
+    works = [s + (rng.standard_normal(P) * 1e-3).astype(f) for s in starts]
+    a = [_dev(x) for x in base]
+    b = [_dev(x) for x in base]
+    A.k_dn_group(a[0], a[1], a[2], [_dev(s) for s in starts], [_dev(w) for w in works], None, N, 1, 0.7, 0.9)
+    for j in range(5):
+        A.k_dn_group(b[0], b[1], b[2], [_dev(starts[j])], [_dev(works[j])], None, N, 1 + j, 0.7, 0.9)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+
+
+@pytest.mark.parametrize("P,Pd", [(0, 0), (3, 2), (1024, 1024), (4 * 256 * 19 + 2, 4 * 256 * 19 - 4), (1 << 20, (1 << 20) - 64)])
+def test_adamw_matches_oracle(P, Pd):
+    rng = np.random.default_rng(P)
+    f = np.float32
+    theta = (rng.standard_normal(P) * 0.02).astype(f)
+    opt = AdamW(P, f, wd=0.1, n_decayed=Pd)
+    th, m, v = _dev(theta), torch.zeros(max(P, 1), device=DEV)[:P], torch.zeros(max(P, 1), device=DEV)[:P]
+    lp = torch.zeros(max(P, 1), dtype=torch.bfloat16, device=DEV)
+    ref = theta.copy()
+    for step in range(1, 6):
+        g = (rng.standard_normal(P) * 10 ** rng.uniform(-6, 0)).astype(f)
+        if P > 10:
+            g[::7] = 0.0
+        A.k_adamw(th, _dev(g), m, v, lp, Pd, step, 1e-3)
+        opt.step(ref, g, 1e-3)
+    torch.cuda.synchronize()
+    if P:
+        np.testing.assert_allclose(th.cpu().numpy(), ref, rtol=2e-6, atol=1e-9)
+        np.testing.assert_allclose(m.cpu().numpy(), opt.m, rtol=1e-5, atol=1e-8)
+        np.testing.assert_allclose(v.cpu().numpy(), opt.v, rtol=1e-5, atol=1e-15)
+        assert torch.equal(lp[:P], th.to(torch.bfloat16))
+
+
+@pytest.mark.parametrize("M,N,K", [(64, 64, 16), (70, 33, 19), (256, 192, 128), (1, 5, 300)])
+@pytest.mark.parametrize("al,bl", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+def test_gemm_generic(M, N, K, al, bl, dt):
+    rng = np.random.default_rng(M * N + K)
+    a = rng.standard_normal((M, K)).astype(np.float32)
+    b = rng.standard_normal((K, N)).astype(np.float32)
+    ad = _dev(a if al == 0 else a.T.copy(), dt)
+    bd = _dev(b if bl == 0 else b.T.copy(), dt)
+    c = torch.empty(M, N, dtype=torch.float32, device=DEV)
+    A.k_gemm(ad, bd, c, M, N, K, al, bl)
+    torch.cuda.synchronize()
+    ar = (ad.float().cpu().numpy() if al == 0 else ad.float().cpu().numpy().T).astype(np.float64)
+    br = (bd.float().cpu().numpy() if bl == 0 else bd.float().cpu().numpy().T).astype(np.float64)
+    np.testing.assert_allclose(c.cpu().numpy(), ar @ br, rtol=1e-5, atol=1e-4)
+
+
+def _attention_case(B, S, h, dh, dt, use_mfma):
+    rng = np.random.default_rng(S + dh)
+    d = h * dh
+    qkv = _dev(rng.standard_normal((B * S, 3 * d)).astype(np.float32), dt)
+    d_o = _dev(rng.standard_normal((B * S, d)).astype(np.float32) * 0.1, dt)
+    o = torch.empty(B * S, d, dtype=dt, device=DEV)
+    lse = torch.empty(B * h * S, dtype=torch.float32, device=DEV)
+    dq = torch.empty_like(qkv)
+    scratch = torch.empty(B * h * S, dtype=torch.float32, device=DEV)
+    A.k_attention_fwd(qkv, o, lse, B, S, h, dh, use_mfma)
+    A.k_attention_bwd(qkv, o, d_o, lse, scratch, dq, B, S, h, dh, use_mfma)
+    torch.cuda.synchronize()
+    x = qkv.float().cpu().numpy().astype(np.float64)
+    split = lambda z: z.reshape(B, S, h, dh).transpose(0, 2, 1, 3)
+    q, k, v = split(x[:, :d]), split(x[:, d:2 * d]), split(x[:, 2 * d:])
+    oo, p = lm.attention_fwd(q, k, v)
+    do4 = split(d_o.float().cpu().numpy().astype(np.float64))
+    rdq, rdk, rdv = lm.attention_bwd(do4, q, k, v, p)
+    merge = lambda z: z.transpose(0, 2, 1, 3).reshape(B * S, d)
+    ref_dqkv = np.concatenate([merge(rdq), merge(rdk), merge(rdv)], axis=1)
+    s = np.matmul(q, np.swapaxes(k, -1, -2)) / np.sqrt(dh)
+    s = np.where(np.triu(np.ones((S, S), bool), 1), -np.inf, s)
+    ref_lse = np.log(np.sum(np.exp(s - s.max(-1, keepdims=True)), -1)) + s.max(-1)
+    return (o.float().cpu().numpy(), merge(oo), lse.cpu().numpy().reshape(B, h, S), ref_lse,
+            dq.float().cpu().numpy(), ref_dqkv)
+
+
+@pytest.mark.parametrize("B,S,h,dh", [(2, 32, 2, 32), (1, 70, 3, 64), (2, 130, 1, 64), (1, 1, 1, 32)])
+@pytest.mark.parametrize("dt", [torch.float32, torch.bfloat16])
+def test_attention_generic(B, S, h, dh, dt):
+    o, ro, lse, rlse, dq, rdq = _attention_case(B, S, h, dh, dt, False)
+    tol = 2e-5 if dt == torch.float32 else 2e-2
+    assert _rel(o, ro) < tol
+    np.testing.assert_allclose(lse, rlse, rtol=1e-5, atol=1e-5)
+    assert _rel(dq, rdq) < tol
+
+
+@pytest.mark.parametrize("M,N,K", [(128, 128, 64), (256, 256, 128), (512, 384, 192), (2048, 4096, 256), (4096, 512, 512)])
+@pytest.mark.parametrize("al,bl", [(0, 0), (0, 1)])
+@pytest.mark.parametrize("odt", [torch.float32, torch.bfloat16])
+def test_gemm_mfma_forward_and_input_gradient_layouts(M, N, K, al, bl, odt):
+    rng = np.random.default_rng(M + N + K)
+    a = rng.standard_normal((M, K)).astype(np.float32)
+    b = rng.standard_normal((K, N)).astype(np.float32)
+    ad = _dev(a, torch.bfloat16)
+    bd = _dev(b if bl == 0 else b.T.copy(), torch.bfloat16)
+    c = torch.full((M, N), float("nan"), dtype=odt, device=DEV)
+    A.k_gemm(ad, bd, c, M, N, K, al, bl, use_mfma=True)
+    torch.cuda.synchronize()
+    ar = ad.float().cpu().numpy().astype(np.float64)
+    br = bd.float().cpu().numpy().astype(np.float64)
+    ref = ar @ (br if bl == 0 else br.T)
+    got = c.float().cpu().numpy()
+    if odt == torch.float32:
+        np.testing.assert_allclose(got, ref, rtol=1e-4, atol=1e-3)
+    else:
+        np.testing.assert_allclose(got, ref, rtol=1e-2, atol=1e-2)
+
+
+@pytest.mark.parametrize("M,N,K", [(128, 128, 64), (256, 384, 4096), (512, 1536, 16384), (896, 3584, 2048)])
+def test_gemm_mfma_weight_gradient_layout(M, N, K):
+    rng = np.random.default_rng(M + N + K)
+    x = rng.standard_normal((K, M)).astype(np.float32)        # stored [K, M]
+    dy = rng.standard_normal((K, N)).astype(np.float32)       # stored [K, N]
+    xd, dyd = _dev(x, torch.bfloat16), _dev(dy, torch.bfloat16)
+    ref = xd.float().cpu().numpy().astype(np.float64).T @ dyd.float().cpu().numpy().astype(np.float64)
+    ws = torch.empty(8 * M * N, dtype=torch.float32, device=DEV)      # room for 8 split-K partials
+    for scratch in (None, ws):
+        c = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
+        A.k_gemm(xd, dyd, c, M, N, K, 1, 0, use_mfma=True, ws=scratch)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(c.cpu().numpy(), ref, rtol=1e-4, atol=2e-3 * np.sqrt(K / 64))
+
+
+def test_gemm_mfma_rejects_unsupported_shapes():
+    a = torch.zeros(100, 64, dtype=torch.bfloat16, device=DEV)
+    b = torch.zeros(64, 128, dtype=torch.bfloat16, device=DEV)
+    c = torch.zeros(100, 128, dtype=torch.float32, device=DEV)
+    with pytest.raises(A.AlsError):
+        A.k_gemm(a, b, c, 100, 128, 64, 0, 0, use_mfma=True)
+    with pytest.raises(A.AlsError):
+        A.k_gemm(a.float(), b.float(), c, 128, 128, 64, 0, 0, use_mfma=True)
+
+
+@pytest.mark.parametrize("B,S,h", [(2, 128, 2), (1, 256, 3), (1, 384, 1), (2, 512, 2), (1, 1024, 1)])
+def test_attention_mfma(B, S, h):
+    o, ro, lse, rlse, dq, rdq = _attention_case(B, S, h, 64, torch.bfloat16, True)
+    assert _rel(o, ro) < 1e-2
+    np.testing.assert_allclose(lse, rlse, rtol=1e-4, atol=1e-4)
+    d = h * 64
+    for nm, sl in (("dq", slice(0, d)), ("dk", slice(d, 2 * d)), ("dv", slice(2 * d, 3 * d))):
+        assert _rel(dq[:, sl], rdq[:, sl]) < 1.5e-2, nm
+
+
+def test_attention_mfma_matches_generic_kernel_closely():
+    # same bf16 inputs through both GPU kernels: they differ only by rounding of P to bf16
+    B, S, h = 1, 256, 2
+    o1, _, l1, _, g1, _ = _attention_case(B, S, h, 64, torch.bfloat16, True)
+    o2, _, l2, _, g2, _ = _attention_case(B, S, h, 64, torch.bfloat16, False)
+    assert _rel(o1, o2) < 1e-2 and _rel(g1, g2) < 1.5e-2
+    np.testing.assert_allclose(l1, l2, rtol=1e-4, atol=1e-4)
