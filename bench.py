@@ -1,0 +1,144 @@
+"""Benchmark of the asynchronous Local-SGD hot path on one MI355X.
+
+A "step" is one outer round of the paper's asynchronous schedule on the 20M-class workload:
+N = 4 sync events (pseudo-gradient + Delayed Nesterov + restart) together with the local rounds
+(DyLU step counts 20/25/33/50, each step = forward + backward + AdamW on 32 x 512 tokens) of the
+four simulated workers, which run on their own HIP streams.  Tokens are synthetic Zipf(1.1)
+draws, resident in HBM before the clock starts.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def flops_per_token(w):
+    """Algorithmic training FLOPs per token: 3 x [L (24 d^2 + 2 S d) + 2 d V] (causal attention
+    counted at half, backward = 2 x forward, no recompute credit)."""
+    L, d, S, V = w["L"], w["d"], w["S"], w["V"]
+    return 3.0 * (L * (24.0 * d * d + 2.0 * S * d) + 2.0 * d * V)
+
+
+def cpu_baseline(w, seconds_hint=20.0):
+    """The oracle as it stands, timed on the host: one local step (forward, backward, AdamW) of
+    worker 0 on a slice of its batch, sized to take roughly 10-30 s."""
+    import numpy as np
+    import als_inputs as I
+    from oracle import lm
+    from oracle.optim import AdamW
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    nb = max(1, w["B"] // 8)
+    theta = I.theta0(lm.param_layout(w), w["seed"])
+    tok = I.TokenStream(w["seed"], 0, w["B"], w["S"], w["V"]).take(1)[0][:nb]
+    opt = AdamW(theta.size, np.float32, w["beta1"], w["beta2"], w["adam_eps"], w["wd"], lm.n_decayed(w))
+    t0 = time.perf_counter()
+    _loss, grad = lm.loss_and_grad(theta, tok, w)
+    opt.step(theta, grad, w["lr"])
+    dt = time.perf_counter() - t0
+    return dict(value=nb * w["S"] / dt, unit="tokens/s", cores=int(threads), kind="oracle",
+                sample=f"1 local step (forward+backward+AdamW, numpy fp32) of worker 0 on {nb} of its "
+                       f"{w['B']} sequences of {w['S']} tokens; {dt:.1f} s on {os.cpu_count()} host cpus")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="lm20m")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the simulated workers are replicas on HIP streams of "
+              "a single MI355X); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import als_inputs as I
+    import paper_2401_09135_amd as A
+
+    w = I.workload(args.workload)
+    k, N = w["k"], w["N"]
+    n_rounds = args.warmup + args.steps
+    n_events = n_rounds * N
+    steps, ev_w, ev_t, ev_g = A.dylu_schedule(w["speeds"], w["H"], w["tau_grace"], n_events)
+    cfg = A.Config.from_workload(w, max_local_steps=int(steps.max()))
+    # parameter layout from the library itself; values N(0, 0.02), gains 1
+    P, Pd = A.param_count(cfg), A.param_count_decayed(cfg)
+    theta0 = I.theta0([("decayed", (Pd,), "matrix"), ("gains", (P - Pd,), "gain")], w["seed"])
+    ctx = A.Context(cfg, theta0)
+
+    # how many local rounds each worker starts: the first one plus one per sync event of its own
+    rounds = [1 + int((ev_w == i).sum()) for i in range(k)]
+    toks = []
+    for i in range(k):
+        st = I.TokenStream(w["seed"], i, w["B"], w["S"], w["V"])
+        toks.append([torch.from_numpy(st.take(int(steps[i]))).to(ctx.device) for _ in range(rounds[i])])
+    nxt = [0] * k
+
+    def train(i):
+        ctx.worker_local_steps(i, toks[i][nxt[i]], w["lr"])
+        nxt[i] += 1
+
+    def run_events(e0, e1):
+        tokens = 0
+        e = e0
+        while e < e1:
+            j = e
+            while j < e1 - 1 and not ev_g[j]:
+                j += 1
+            group = [int(x) for x in ev_w[e:j + 1]]
+            ctx.outer_apply_dn(group, restart=True)
+            for i in group:
+                tokens += int(steps[i]) * w["B"] * w["S"]
+                train(i)
+            e = j + 1
+        return tokens
+
+    for i in range(k):
+        train(i)
+    run_events(0, args.warmup * N)
+    ctx.sync()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    tokens = run_events(args.warmup * N, n_events)
+    ctx.sync()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    tok_s = tokens / dt
+    tflops = tok_s * flops_per_token(w) / 1e12
+    out = dict(metric="simulated-worker training tokens/s/GPU", value=tok_s, unit="tokens/s", n_gpus=1,
+               steps=args.steps, warmup=args.warmup, ms_per_step=1e3 * dt / max(args.steps, 1),
+               higher_is_better=True, scaling="weak", vs_baseline=None, dtype="bf16" if w["dtype"] == "bf16" else "f32",
+               data="synthetic",
+               config=dict(workload=f"{args.workload}: L{w['L']} d{w['d']} h{w['h']} ff{w['ff']} V{w['V']} S{w['S']} "
+                                    f"B{w['B']}/worker, k={k} workers speeds {np.round(w['speeds'], 3).tolist()}, "
+                                    f"DyLU H={w['H']} -> {steps.tolist()}, DN N={N} beta={w['outer_beta']} "
+                                    f"eps={w['outer_lr']}, step = one outer round of N sync events",
+                           tokens_per_step=tokens // max(args.steps, 1),
+                           model_tflops=tflops, mfma_frac_whole_path=tflops / PEAK_BF16_TFLOPS),
+               roofline=None, cpu_baseline=None)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    ctx.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -174,6 +174,10 @@ int als_k_adamw(float* theta, const float* grad, float* m, float* v, void* bf16_
 int als_k_gemm(const void* A, const void* B, void* C, int M, int N, int K, int a_layout,
                int b_layout, int in_dtype, int out_dtype, int use_mfma, void* ws_dev,
                size_t ws_bytes, void* stream);
+/* Benchmark hook: force the MFMA GEMM tile to 256x256, 256x128 or 128x128 with nbuf = 2
+ * (LDS double buffer) or 1 (single buffer, more workgroups per CU); 0,0,0 = automatic choice
+ * by shape.  Process-wide, not thread-safe. */
+int als_k_set_gemm_tile(int bm, int bn, int nbuf);
 /* Causal attention forward / backward on packed qkv [B*S, 3d] (q|k|v, head-major), dtype
  * ALS_DTYPE_*: o [B*S,d] same dtype, lse fp32 [B,h,S]; backward takes d_o and returns dqkv. */
 int als_k_attention_fwd(const void* qkv, void* o, float* lse, int B, int S, int h, int dh,

@@ -60,19 +60,19 @@ __device__ __forceinline__ int tr_off(int lane, int rb, int cb) {
 }
 
 // copy a [64 rows][64] bf16 tile from global (row pitch ld elements) to registers / LDS
-struct TileRegs { uint4 r[2]; };
+struct TileRegs { u32x4 r[2]; };
 __device__ __forceinline__ void tile_load(TileRegs& t, const bf16* src, int64_t ld, int tid) {
 #pragma unroll
   for (int i = 0; i < 2; i++) {
     int c = tid + i * 256;
-    t.r[i] = *reinterpret_cast<const uint4*>(src + (int64_t)(c >> 3) * ld + (c & 7) * 8);
+    t.r[i] = *reinterpret_cast<const u32x4*>(src + (int64_t)(c >> 3) * ld + (c & 7) * 8);
   }
 }
 __device__ __forceinline__ void tile_store(const TileRegs& t, char* dst, int tid) {
 #pragma unroll
   for (int i = 0; i < 2; i++) {
     int c = tid + i * 256;
-    *reinterpret_cast<uint4*>(dst + (c >> 3) * ROW_D + (c & 7) * 16) = t.r[i];
+    *reinterpret_cast<u32x4*>(dst + (c >> 3) * ROW_D + (c & 7) * 16) = t.r[i];
   }
 }
 

@@ -264,7 +264,7 @@ int embed_fwd(const int32_t* tok, const float* E, const float* Ppos, float* x, i
 //     the positions holding token v inside pos[].  It depends on the tokens only, so one
 //     launch prepares every step of a local round.
 // (2) embed_bwd_rows: one workgroup per vocabulary row adds the dx rows of its positions
-//     (wave w takes every 4th position, the four partial rows are added in a fixed order)
+//     (wave w of 16 takes every 16th position, the partial rows are added in a fixed order)
 //     and writes the row, zeros included.
 // dPpos[s,:] = sum_b dx[b,s,:] in batch order.
 __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
@@ -343,23 +343,29 @@ int embed_sort(const int32_t* tok, int n_steps, int B, int S, int V, int32_t* of
 }
 
 #define EMB_MAXD4 4  // float4 slots per lane: d <= 1024
-__global__ __launch_bounds__(256) void embed_bwd_rows_kernel(const int32_t* __restrict__ offset,
-                                                             const int32_t* __restrict__ pos,
-                                                             const float* __restrict__ dx,
-                                                             float* __restrict__ dE, int d) {
-  extern __shared__ float smem[];  // [4][d]
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void embed_bwd_rows_kernel(const int32_t* __restrict__ offset,
+                                                                 const int32_t* __restrict__ pos,
+                                                                 const float* __restrict__ dx,
+                                                                 float* __restrict__ dE, int d) {
+  extern __shared__ float smem[];  // [NW][d]
   const int v = blockIdx.x, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int beg = offset[v], end = offset[v + 1];
   const int d4 = d / 4;
   float4* out = reinterpret_cast<float4*>(dE + (int64_t)v * d);
   if (beg == end) {
-    for (int c = threadIdx.x; c < d4; c += 256) out[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int c = threadIdx.x; c < d4; c += 64 * NW) out[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+    return;
+  }
+  if (end - beg == 1) {  // a single position: copy its row
+    const float4* row = reinterpret_cast<const float4*>(dx + (int64_t)pos[beg] * d);
+    for (int c = threadIdx.x; c < d4; c += 64 * NW) out[c] = row[c];
     return;
   }
   float4 acc[EMB_MAXD4];
 #pragma unroll
   for (int s = 0; s < EMB_MAXD4; s++) acc[s] = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int r = beg + w; r < end; r += 4) {
+  for (int r = beg + w; r < end; r += NW) {
     const float4* row = reinterpret_cast<const float4*>(dx + (int64_t)pos[r] * d);
 #pragma unroll
     for (int s = 0; s < EMB_MAXD4; s++) {
@@ -376,8 +382,12 @@ __global__ __launch_bounds__(256) void embed_bwd_rows_kernel(const int32_t* __re
     if (c < d4) reinterpret_cast<float4*>(smem + w * d)[c] = acc[s];
   }
   __syncthreads();
-  for (int c = threadIdx.x; c < d; c += 256)
-    dE[(int64_t)v * d + c] = ((smem[c] + smem[d + c]) + smem[2 * d + c]) + smem[3 * d + c];
+  for (int c = threadIdx.x; c < d; c += 64 * NW) {
+    float t = smem[c];
+#pragma unroll
+    for (int i = 1; i < NW; i++) t += smem[i * d + c];
+    dE[(int64_t)v * d + c] = t;
+  }
 }
 
 __global__ void embed_bwd_pos_kernel(const float* __restrict__ dx, float* __restrict__ dPpos,
@@ -393,8 +403,10 @@ __global__ void embed_bwd_pos_kernel(const float* __restrict__ dx, float* __rest
 int embed_bwd(const int32_t* offset, const int32_t* pos, const float* dx, float* dE, float* dPpos,
               int B, int S, int d, int V, hipStream_t st) {
   if (d > 256 * EMB_MAXD4 || d % 4) return set_error(ALS_ERR_INVALID, "embed_bwd: d unsupported");
-  hipLaunchKernelGGL(embed_bwd_rows_kernel, dim3(V), dim3(256), (size_t)4 * d * sizeof(float), st, offset,
-                     pos, dx, dE, d);
+  // 16 wavefronts per vocabulary row so that the few very frequent tokens (Zipf) finish soon;
+  // [16][d] floats of LDS fit the default 64 KiB up to d = 1024
+  hipLaunchKernelGGL(embed_bwd_rows_kernel<16>, dim3(V), dim3(1024), (size_t)16 * d * sizeof(float), st,
+                     offset, pos, dx, dE, d);
   ALS_CHECK_LAUNCH();
   int threads = d < 256 ? d : 256;
   hipLaunchKernelGGL(embed_bwd_pos_kernel, dim3(S), dim3(threads), 0, st, dx, dPpos, B, S, d);
@@ -506,18 +518,29 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(
     partial[(int64_t)blockIdx.x * d + c] = smem[c] + smem[d + c] + smem[2 * d + c] + smem[3 * d + c];
 }
 
-__global__ void sum_partials_kernel(const float* __restrict__ partial, float* __restrict__ out,
-                                    int nblk, int d) {
-  int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= d) return;
+// out[c] = sum_b partial[b][c]: 32 columns per block, 8 row groups each adding every 8th
+// partial, combined in a fixed order.
+__global__ __launch_bounds__(256) void sum_partials_kernel(const float* __restrict__ partial,
+                                                           float* __restrict__ out, int nblk, int d) {
+  __shared__ float sh[8][33];
+  int cl = threadIdx.x & 31, rg = threadIdx.x >> 5;
+  int c = blockIdx.x * 32 + cl;
   float acc = 0.0f;
-  for (int b = 0; b < nblk; b++) acc += partial[(int64_t)b * d + c];
-  out[c] = acc;
+  if (c < d)
+    for (int b = rg; b < nblk; b += 8) acc += partial[(int64_t)b * d + c];
+  sh[rg][cl] = acc;
+  __syncthreads();
+  if (rg == 0 && c < d) {
+    float t = sh[0][cl];
+#pragma unroll
+    for (int r = 1; r < 8; r++) t += sh[r][cl];
+    out[c] = t;
+  }
 }
 
 int rmsnorm_bwd_blocks(int T) {
   int b = (T + 3) / 4;
-  return b > 512 ? 512 : b;
+  return b > 256 ? 256 : b;
 }
 
 int rmsnorm_bwd(const float* dy, const float* x, const float* rstd, const float* g,
@@ -533,7 +556,7 @@ int rmsnorm_bwd(const float* dy, const float* x, const float* rstd, const float*
     hipLaunchKernelGGL(rmsnorm_bwd_kernel<float>, dim3(nblk), dim3(256), sm, st, dy, x, rstd, g, dx_in,
                        dx_out, (float*)dx_lp, partial, T, d);
   ALS_CHECK_LAUNCH();
-  hipLaunchKernelGGL(sum_partials_kernel, dim3((d + 63) / 64), dim3(64), 0, st, partial, dg, nblk, d);
+  hipLaunchKernelGGL(sum_partials_kernel, dim3((d + 31) / 32), dim3(256), 0, st, partial, dg, nblk, d);
   ALS_CHECK_LAUNCH();
   return ALS_OK;
 }
@@ -582,10 +605,78 @@ __global__ __launch_bounds__(256) void cross_entropy_kernel(const float* __restr
   }
 }
 
+// Same, reading the row once: each thread keeps up to 32 logits (8 float4) in registers, so a
+// block of BS threads covers V <= 32 BS.
+template <typename OT, int BS>
+__global__ __launch_bounds__(BS) void cross_entropy_reg_kernel(const float* __restrict__ logits,
+                                                               const int32_t* __restrict__ tok,
+                                                               float* __restrict__ loss_row,
+                                                               OT* __restrict__ dl, int S, int V, float invT) {
+  __shared__ float sh[16];
+  int t = blockIdx.x;
+  int b = t / S, s = t % S;
+  int tgt = tok[(int64_t)b * (S + 1) + s + 1];
+  tgt = tgt < 0 ? 0 : (tgt >= V ? V - 1 : tgt);
+  const f32x4* lr = reinterpret_cast<const f32x4*>(logits + (int64_t)t * V);
+  const int v4 = V / 4;
+  f32x4 x[8];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < 8; i++) {
+    int c = threadIdx.x + i * BS;
+    if (c < v4) {
+      x[i] = lr[c];
+      mx = fmaxf(fmaxf(mx, fmaxf(x[i][0], x[i][1])), fmaxf(x[i][2], x[i][3]));
+    }
+  }
+  mx = block_reduce(mx, true, sh);
+  float sum = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 8; i++) {
+    int c = threadIdx.x + i * BS;
+    if (c < v4) {
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        x[i][e] = expf(x[i][e] - mx);
+        sum += x[i][e];
+      }
+    }
+  }
+  sum = block_reduce(sum, false, sh);
+  float inv = 1.0f / sum;
+  if (threadIdx.x == 0) loss_row[t] = mx + logf(sum) - logits[(int64_t)t * V + tgt];
+  OT* dr = dl + (int64_t)t * V;
+#pragma unroll
+  for (int i = 0; i < 8; i++) {
+    int c = threadIdx.x + i * BS;
+    if (c < v4) {
+      float4 p = make_float4(x[i][0] * inv, x[i][1] * inv, x[i][2] * inv, x[i][3] * inv);
+      int k = tgt - 4 * c;
+      if (k == 0) p.x -= 1.0f;
+      if (k == 1) p.y -= 1.0f;
+      if (k == 2) p.z -= 1.0f;
+      if (k == 3) p.w -= 1.0f;
+      p.x *= invT; p.y *= invT; p.z *= invT; p.w *= invT;
+      if (sizeof(OT) == 2) store_bf16x4(reinterpret_cast<bf16*>(dr) + 4 * c, p);
+      else reinterpret_cast<float4*>(dr)[c] = p;
+    }
+  }
+}
+
 int cross_entropy(const float* logits, const int32_t* tok, float* loss_row, void* dlogits,
                   int dl_bf16, int B, int S, int V, hipStream_t st) {
   int T = B * S;
   float invT = 1.0f / (float)T;
+  if (dl_bf16 && V % 4 == 0 && V <= 32 * 1024) {
+    if (V <= 32 * 256)
+      hipLaunchKernelGGL((cross_entropy_reg_kernel<bf16, 256>), dim3(T), dim3(256), 0, st, logits, tok,
+                         loss_row, (bf16*)dlogits, S, V, invT);
+    else
+      hipLaunchKernelGGL((cross_entropy_reg_kernel<bf16, 1024>), dim3(T), dim3(1024), 0, st, logits, tok,
+                         loss_row, (bf16*)dlogits, S, V, invT);
+    ALS_CHECK_LAUNCH();
+    return ALS_OK;
+  }
   if (dl_bf16)
     hipLaunchKernelGGL(cross_entropy_kernel<bf16>, dim3(T), dim3(256), 0, st, logits, tok, loss_row,
                        (bf16*)dlogits, S, V, invT);

@@ -24,7 +24,7 @@ namespace {
 
 constexpr int BK = 64;
 
-template <int BM, int BN, int AL, int BL>
+template <int BM, int BN, int AL, int BL, int NBUF>
 struct Tile {
   // AL == 0: A tile kept as [BM rows][64 k] ; AL == 1: as [64 k][BM rows]
   static constexpr int A_STRIDE = AL == 0 ? BK * 2 + 16 : BM * 2 + 32;
@@ -33,7 +33,7 @@ struct Tile {
   static constexpr int B_STRIDE = BL == 1 ? BK * 2 + 16 : BN * 2 + 32;
   static constexpr int B_BYTES = B_STRIDE * (BL == 1 ? BN : BK);
   static constexpr int STAGE = A_BYTES + B_BYTES;
-  static constexpr int LDS_BYTES = 2 * STAGE;
+  static constexpr int LDS_BYTES = NBUF * STAGE;
   static constexpr int A_CHUNKS = BM * BK * 2 / 16 / 256;  // 16-byte chunks per thread
   static constexpr int B_CHUNKS = BN * BK * 2 / 16 / 256;
 };
@@ -53,13 +53,19 @@ __device__ __forceinline__ bf16x8 lds_read_tr(const char* p, int stride) {
   return __builtin_bit_cast(bf16x8, r);
 }
 
+// tanh through the hardware exp2 and reciprocal: 1 - 2 / (1 + e^{2y}); absolute error of a
+// few 1e-7, far below the bf16 rounding of the values it multiplies
+__device__ __forceinline__ float fast_tanh(float y) {
+  float e = __builtin_amdgcn_exp2f(y * 2.8853900817779268f);  // e^{2y}
+  return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + e);
+}
 __device__ __forceinline__ float gelu_f(float u) {
   const float a = 0.7978845608028654f, b = 0.044715f;
-  return 0.5f * u * (1.0f + tanhf(a * (u + b * u * u * u)));
+  return 0.5f * u * (1.0f + fast_tanh(a * (u + b * u * u * u)));
 }
 __device__ __forceinline__ float gelu_grad_f(float u) {
   const float a = 0.7978845608028654f, b = 0.044715f;
-  float th = tanhf(a * (u + b * u * u * u));
+  float th = fast_tanh(a * (u + b * u * u * u));
   return 0.5f * (1.0f + th) + 0.5f * u * (1.0f - th * th) * a * (1.0f + 3.0f * b * u * u);
 }
 
@@ -74,9 +80,12 @@ struct MfmaArgs {
   int64_t split_stride;  // elements between split partials (split-K only)
 };
 
-template <int BM, int BN, int AL, int BL, int EPI, typename TO, bool SPLIT>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(MfmaArgs g) {
-  typedef Tile<BM, BN, AL, BL> TL;
+// NBUF = 2: LDS double buffer, one barrier per K slice, one workgroup per CU for the large
+// tiles.  NBUF = 1: single LDS buffer, two barriers per slice, but half the LDS so that OCC
+// workgroups share a CU and one's epilogue and barrier stalls hide behind another's MFMAs.
+template <int BM, int BN, int AL, int BL, int EPI, typename TO, bool SPLIT, int NBUF, int OCC>
+__global__ __launch_bounds__(256, OCC) void gemm_mfma_kernel(MfmaArgs g) {
+  typedef Tile<BM, BN, AL, BL, NBUF> TL;
   constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -94,7 +103,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(MfmaArgs g) {
   const bf16* Ag = AL == 0 ? g.A + (int64_t)m0 * g.lda + kbase : g.A + kbase * g.lda + m0;
   const bf16* Bg = BL == 1 ? g.B + (int64_t)n0 * g.ldb + kbase : g.B + kbase * g.ldb + n0;
 
-  uint4 ra[TL::A_CHUNKS], rb[TL::B_CHUNKS];
+  u32x4 ra[TL::A_CHUNKS], rb[TL::B_CHUNKS];
 
   auto load_global = [&](int kt) {
 #pragma unroll
@@ -103,7 +112,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(MfmaArgs g) {
       const bf16* p;
       if (AL == 0) p = Ag + (int64_t)(c >> 3) * g.lda + kt * BK + (c & 7) * 8;
       else p = Ag + (int64_t)(kt * BK + c / (BM / 8)) * g.lda + (c % (BM / 8)) * 8;
-      ra[i] = *reinterpret_cast<const uint4*>(p);
+      ra[i] = *reinterpret_cast<const u32x4*>(p);
     }
 #pragma unroll
     for (int i = 0; i < TL::B_CHUNKS; i++) {
@@ -111,7 +120,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(MfmaArgs g) {
       const bf16* p;
       if (BL == 1) p = Bg + (int64_t)(c >> 3) * g.ldb + kt * BK + (c & 7) * 8;
       else p = Bg + (int64_t)(kt * BK + c / (BN / 8)) * g.ldb + (c % (BN / 8)) * 8;
-      rb[i] = *reinterpret_cast<const uint4*>(p);
+      rb[i] = *reinterpret_cast<const u32x4*>(p);
     }
   };
   auto store_lds = [&](int buf) {
@@ -122,14 +131,14 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(MfmaArgs g) {
       int c = tid + i * 256;
       int off = AL == 0 ? (c >> 3) * TL::A_STRIDE + (c & 7) * 16
                         : (c / (BM / 8)) * TL::A_STRIDE + (c % (BM / 8)) * 16;
-      *reinterpret_cast<uint4*>(As + off) = ra[i];
+      *reinterpret_cast<u32x4*>(As + off) = ra[i];
     }
 #pragma unroll
     for (int i = 0; i < TL::B_CHUNKS; i++) {
       int c = tid + i * 256;
       int off = BL == 1 ? (c >> 3) * TL::B_STRIDE + (c & 7) * 16
                         : (c / (BN / 8)) * TL::B_STRIDE + (c % (BN / 8)) * 16;
-      *reinterpret_cast<uint4*>(Bs + off) = rb[i];
+      *reinterpret_cast<u32x4*>(Bs + off) = rb[i];
     }
   };
 
@@ -148,56 +157,106 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(MfmaArgs g) {
   if (BL == 1) b_off = (wn * WN + (lane & 31)) * TL::B_STRIDE + (lane >> 5) * 16;
   else b_off = ((lane >> 5) * 8 + ((lane & 15) >> 2)) * TL::B_STRIDE + (wn * WN + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;
 
-  const int nk = g.K / BK;
-  load_global(0);
-  store_lds(0);
-  __syncthreads();
-  for (int kt = 0; kt < nk; kt++) {
-    if (kt + 1 < nk) load_global(kt + 1);
-    const char* As = smem + (kt & 1) * TL::STAGE;
-    const char* Bs = As + TL::A_BYTES;
+  // The products are formed transposed (B fragment as the MFMA's first operand), so that an
+  // accumulator holds, for ONE row m = lane % 32 of C, columns 8 g + 4 (lane / 32) + 0..3:
+  // the epilogue then moves 4 consecutive columns per access.
+  // Fragments are double-buffered in registers: the LDS reads of 16-wide step kk+1 are issued
+  // ahead of the MFMAs of step kk and interleaved with them, one read per few MFMAs.
+  auto read_frags = [&](const char* As, const char* Bs, int kk, bf16x8 (&af)[TM], bf16x8 (&bfr)[TN]) {
+#pragma unroll
+    for (int i = 0; i < TM; i++) {
+      if (AL == 0) af[i] = lds_read_direct(As + a_off + i * 32 * TL::A_STRIDE + kk * 32);
+      else af[i] = lds_read_tr(As + a_off + kk * 16 * TL::A_STRIDE + i * 64, TL::A_STRIDE);
+    }
+#pragma unroll
+    for (int j = 0; j < TN; j++) {
+      if (BL == 1) bfr[j] = lds_read_direct(Bs + b_off + j * 32 * TL::B_STRIDE + kk * 32);
+      else bfr[j] = lds_read_tr(Bs + b_off + kk * 16 * TL::B_STRIDE + j * 64, TL::B_STRIDE);
+    }
+  };
+  auto compute = [&](const char* As, const char* Bs) {
+    bf16x8 af[2][TM], bfr[2][TN];
+    read_frags(As, Bs, 0, af[0], bfr[0]);
 #pragma unroll
     for (int kk = 0; kk < BK / 16; kk++) {
-      bf16x8 af[TM], bfr[TN];
-#pragma unroll
-      for (int i = 0; i < TM; i++) {
-        if (AL == 0) af[i] = lds_read_direct(As + a_off + i * 32 * TL::A_STRIDE + kk * 32);
-        else af[i] = lds_read_tr(As + a_off + kk * 16 * TL::A_STRIDE + i * 64, TL::A_STRIDE);
-      }
-#pragma unroll
-      for (int j = 0; j < TN; j++) {
-        if (BL == 1) bfr[j] = lds_read_direct(Bs + b_off + j * 32 * TL::B_STRIDE + kk * 32);
-        else bfr[j] = lds_read_tr(Bs + b_off + kk * 16 * TL::B_STRIDE + j * 64, TL::B_STRIDE);
-      }
+      if (kk + 1 < BK / 16) read_frags(As, Bs, kk + 1, af[(kk + 1) & 1], bfr[(kk + 1) & 1]);
 #pragma unroll
       for (int i = 0; i < TM; i++)
 #pragma unroll
         for (int j = 0; j < TN; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
+      if (kk + 1 < BK / 16) {
+        constexpr int NREAD = (AL == 0 ? TM : 2 * TM) + (BL == 1 ? TN : 2 * TN);
+        constexpr int PER = (TM * TN) / NREAD > 0 ? (TM * TN) / NREAD : 1;
+#pragma unroll
+        for (int r = 0; r < NREAD; r++) {
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    // one LDS read
+          __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);  // a few MFMAs
+        }
+      }
     }
-    if (kt + 1 < nk) store_lds((kt + 1) & 1);
+  };
+
+  const int nk = g.K / BK;
+  load_global(0);
+  if (NBUF == 2) {
+    store_lds(0);
     __syncthreads();
+    for (int kt = 0; kt < nk; kt++) {
+      if (kt + 1 < nk) load_global(kt + 1);
+      const char* As = smem + (kt & 1) * TL::STAGE;
+      compute(As, As + TL::A_BYTES);
+      if (kt + 1 < nk) store_lds((kt + 1) & 1);
+      __syncthreads();
+    }
+  } else {
+    for (int kt = 0; kt < nk; kt++) {
+      store_lds(0);
+      __syncthreads();
+      if (kt + 1 < nk) load_global(kt + 1);
+      compute(smem, smem + TL::A_BYTES);
+      __syncthreads();
+    }
   }
 
-  // epilogue
+  // epilogue: 4 consecutive columns per lane and access
   TO* C = reinterpret_cast<TO*>(g.C);
   if (SPLIT) C += (int64_t)blockIdx.z * g.split_stride;
 #pragma unroll
-  for (int i = 0; i < TM; i++)
+  for (int i = 0; i < TM; i++) {
+    const int row = m0 + wm * WM + i * 32 + (lane & 31);
 #pragma unroll
-    for (int j = 0; j < TN; j++) {
-      int col = n0 + wn * WN + j * 32 + (lane & 31);
+    for (int j = 0; j < TN; j++)
 #pragma unroll
-      for (int v = 0; v < 16; v++) {
-        int row = m0 + wm * WM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        int64_t ci = (int64_t)row * g.ldc + col;
-        float x = acc[i][j][v];
-        if (EPI == EPI_RESID) x += g.R[(int64_t)row * g.ldr + col];
-        if (EPI == EPI_DGELU) x *= gelu_grad_f((float)g.U[ci]);
-        C[ci] = (TO)x;
-        if (EPI == EPI_GELU) reinterpret_cast<TO*>(g.C2)[ci] = (TO)gelu_f(x);
+      for (int gq = 0; gq < 4; gq++) {
+        const int col = n0 + wn * WN + j * 32 + 8 * gq + 4 * (lane >> 5);
+        const int64_t ci = (int64_t)row * g.ldc + col;
+        f32x4 x = {acc[i][j][4 * gq], acc[i][j][4 * gq + 1], acc[i][j][4 * gq + 2], acc[i][j][4 * gq + 3]};
+        if (EPI == EPI_RESID) {
+          f32x4 r = *reinterpret_cast<const f32x4*>(g.R + (int64_t)row * g.ldr + col);
+          x += r;
+        }
+        if (EPI == EPI_DGELU) {
+          bf16x4 u = *reinterpret_cast<const bf16x4*>(g.U + ci);
+#pragma unroll
+          for (int e = 0; e < 4; e++) x[e] *= gelu_grad_f((float)u[e]);
+        }
+        if (sizeof(TO) == 4) {
+          *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(C) + ci) = x;
+        } else {
+          bf16x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; e++) o[e] = (bf16)x[e];
+          *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16*>(C) + ci) = o;
+          if (EPI == EPI_GELU) {
+            bf16x4 o2;
+#pragma unroll
+            for (int e = 0; e < 4; e++) o2[e] = (bf16)gelu_f(x[e]);
+            *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16*>(g.C2) + ci) = o2;
+          }
+        }
       }
-    }
+  }
 }
 
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part,
@@ -214,10 +273,10 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
   }
 }
 
-template <int BM, int BN, int AL, int BL, int EPI, typename TO, bool SPLIT>
+template <int BM, int BN, int AL, int BL, int EPI, typename TO, bool SPLIT, int NBUF, int OCC>
 int launch(const MfmaArgs& a, int nsplit, hipStream_t st) {
-  typedef Tile<BM, BN, AL, BL> TL;
-  auto kern = gemm_mfma_kernel<BM, BN, AL, BL, EPI, TO, SPLIT>;
+  typedef Tile<BM, BN, AL, BL, NBUF> TL;
+  auto kern = gemm_mfma_kernel<BM, BN, AL, BL, EPI, TO, SPLIT, NBUF, OCC>;
   static bool attr_set = false;  // idempotent; a race only repeats the call
   if (!attr_set) {
     ALS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -230,7 +289,6 @@ int launch(const MfmaArgs& a, int nsplit, hipStream_t st) {
   return ALS_OK;
 }
 
-// Tile choice: 256-wide tiles when they divide the shape and still give every CU work.
 inline bool fits(int M, int N, int bm, int bn) { return M % bm == 0 && N % bn == 0; }
 
 }  // namespace
@@ -248,14 +306,18 @@ bool gemm_mfma_supported(const GemmDesc& g) {
   return false;
 }
 
-#define ALS_TILE_SWITCH(AL, BL, EPI, TO, SPLIT)                                                  \
-  do {                                                                                           \
-    if (bm == 256 && bn == 256) return launch<256, 256, AL, BL, EPI, TO, SPLIT>(a, nsplit, st);  \
-    if (bm == 256 && bn == 128) return launch<256, 128, AL, BL, EPI, TO, SPLIT>(a, nsplit, st);  \
-    return launch<128, 128, AL, BL, EPI, TO, SPLIT>(a, nsplit, st);                              \
+// tile variants: 256x256 double-buffered (1 workgroup per CU), 256x128 and 128x128 either
+// double-buffered or single-buffered with 2 / 3 workgroups per CU
+#define ALS_TILE_SWITCH(AL, BL, EPI, TO, SPLIT)                                                            \
+  do {                                                                                                     \
+    if (bm == 256 && bn == 256) return launch<256, 256, AL, BL, EPI, TO, SPLIT, 2, 1>(a, nsplit, st);      \
+    if (bm == 256 && bn == 128 && nbuf == 2) return launch<256, 128, AL, BL, EPI, TO, SPLIT, 2, 1>(a, nsplit, st); \
+    if (bm == 256 && bn == 128) return launch<256, 128, AL, BL, EPI, TO, SPLIT, 1, 2>(a, nsplit, st);      \
+    if (nbuf == 2) return launch<128, 128, AL, BL, EPI, TO, SPLIT, 2, 2>(a, nsplit, st);                   \
+    return launch<128, 128, AL, BL, EPI, TO, SPLIT, 1, 3>(a, nsplit, st);                                  \
   } while (0)
 
-static int dispatch(const GemmDesc& g, const MfmaArgs& a, int bm, int bn, int nsplit, hipStream_t st) {
+static int dispatch(const GemmDesc& g, const MfmaArgs& a, int bm, int bn, int nbuf, int nsplit, hipStream_t st) {
   if (g.a_layout == 0 && g.b_layout == 0) {
     if (g.epi == EPI_RESID) ALS_TILE_SWITCH(0, 0, EPI_RESID, float, false);
     if (g.epi == EPI_GELU) ALS_TILE_SWITCH(0, 0, EPI_GELU, bf16, false);
@@ -271,12 +333,18 @@ static int dispatch(const GemmDesc& g, const MfmaArgs& a, int bm, int bn, int ns
   ALS_TILE_SWITCH(1, 0, EPI_STORE, float, false);
 }
 
+static int g_force_bm = 0, g_force_bn = 0, g_force_nbuf = 0;  // tuning override, 0 = automatic
+
 int gemm_mfma(const GemmDesc& g, hipStream_t st) {
   if (!gemm_mfma_supported(g)) return set_error(ALS_ERR_INVALID, "gemm_mfma: unsupported shape or layout");
-  int bm = 128, bn = 128;
-  const int target = 256;  // one tile per CU at least
-  if (fits(g.M, g.N, 256, 256) && (g.M / 256) * (g.N / 256) >= target) { bm = 256; bn = 256; }
-  else if (fits(g.M, g.N, 256, 128) && (g.M / 256) * (g.N / 128) >= target) { bm = 256; bn = 128; }
+  // Tile choice (measured on MI355X): the single-buffered variants, which put 2-3 workgroups
+  // on a CU so that one's prologue/epilogue hides behind another's MFMAs, win on this path's
+  // shapes (short K, M or N large); 256x128 when that still leaves two tiles per CU.
+  int bm = 128, bn = 128, nbuf = 1;
+  const int target = 256;
+  if (g_force_bm && fits(g.M, g.N, g_force_bm, g_force_bn)) { bm = g_force_bm; bn = g_force_bn; nbuf = g_force_nbuf; }
+  else if (g.a_layout == 1) { nbuf = 2; }
+  else if (fits(g.M, g.N, 256, 128) && (g.M / 256) * (g.N / 128) >= 2 * target) { bm = 256; bn = 128; }
   MfmaArgs a;
   a.A = (const bf16*)g.A; a.B = (const bf16*)g.B; a.lda = g.lda; a.ldb = g.ldb;
   a.M = g.M; a.N = g.N; a.K = g.K; a.tiles_m = g.M / bm; a.tiles_n = g.N / bn;
@@ -299,7 +367,7 @@ int gemm_mfma(const GemmDesc& g, hipStream_t st) {
   if (nsplit > 1) {
     a.K = g.K / nsplit;
     a.C = g.ws; a.ldc = g.N; a.split_stride = (int64_t)g.M * g.N;
-    int rc = dispatch(g, a, bm, bn, nsplit, st);
+    int rc = dispatch(g, a, bm, bn, nbuf, nsplit, st);
     if (rc) return rc;
     int64_t n4 = (int64_t)g.M * g.N / 4;
     int blocks = (int)((n4 + 255) / 256 < 4096 ? (n4 + 255) / 256 : 4096);
@@ -308,7 +376,16 @@ int gemm_mfma(const GemmDesc& g, hipStream_t st) {
     ALS_CHECK_LAUNCH();
     return ALS_OK;
   }
-  return dispatch(g, a, bm, bn, 1, st);
+  return dispatch(g, a, bm, bn, nbuf, 1, st);
 }
 
 }  // namespace als
+
+// Tuning hook: force the MFMA GEMM tile (256x256, 256x128 or 128x128) and its LDS buffering
+// (2 = double, 1 = single buffer with more workgroups per CU); 0,0 restores the automatic choice.  Not thread-safe; meant for benchmarks.
+extern "C" int als_k_set_gemm_tile(int bm, int bn, int nbuf) {
+  bool ok = (bm == 0 && bn == 0) || (bm == 256 && bn == 256) || (bm == 256 && bn == 128) || (bm == 128 && bn == 128);
+  if (!ok || (bm && nbuf != 1 && nbuf != 2)) return als::set_error(ALS_ERR_INVALID, "unsupported tile %dx%d/%d", bm, bn, nbuf);
+  als::g_force_bm = bm; als::g_force_bn = bn; als::g_force_nbuf = nbuf;
+  return ALS_OK;
+}
