@@ -39,6 +39,13 @@ WORKLOADS = {
     # seconds, still several GEMM/attention tiles with ragged step counts).
     "mini_bf16": dict(_COMMON, L=2, d=256, h=4, ff=1024, V=1024, S=128, B=4, dtype="bf16",
                       k=4, speeds=[1.0, 1.2, 1.6, 2.4], H=10, N=4, n_events=4),
+    # the 150M-class architecture on one 1024-token sequence per step (d 896 = 7 x 128, 14 heads,
+    # V 32000, S 1024): every kernel shape class of BASELINE configs[3] at 1/16 of its batch
+    "lm150m_b1": dict(_COMMON, L=12, d=896, h=14, ff=3584, V=32000, S=1024, B=1, dtype="bf16",
+                      k=2, speeds=[1.0, 2.0], H=2, N=2, n_events=2),
+    # 16 heterogeneous workers (BASELINE configs[4]'s scheduling shape) on the reduced model
+    "mini_bf16_k16": dict(_COMMON, L=2, d=256, h=4, ff=1024, V=1024, S=128, B=2, dtype="bf16",
+                          k=16, speeds=("uniform", 1.0, 4.0), H=6, N=16, n_events=16),
     "mini_f32": dict(_COMMON, L=2, d=128, h=4, ff=384, V=320, S=48, B=3, dtype="f32",
                      k=3, speeds=[1.0, 2.0, 2.0], H=4, N=3, n_events=6),
 }

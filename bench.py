@@ -54,6 +54,69 @@ def cpu_baseline(w, seconds_hint=20.0):
                        f"{w['B']} sequences of {w['S']} tokens; {dt:.1f} s on {os.cpu_count()} host cpus")
 
 
+def outer_microbench(args):
+    """BASELINE configs[2]: pseudo-gradient + Delayed Nesterov (single events, the grouped pass with
+    fused restart) and fused AdamW on a 150M-element fp32 vector; achieved HBM GB/s from the
+    algorithmic bytes per parameter (DN: 24 non-boundary, 32 boundary, grouped G events with
+    restart 8G + 24 + 10G; AdamW: 30 with fp32 gradient and bf16 copy)."""
+    import numpy as np
+    import torch
+    import als_inputs as I
+    import paper_2401_09135_amd as A
+    mb = I.OUTER_MICROBENCH
+    P, dev = mb["P"], "cuda:0"
+    G = 16
+    gen = torch.Generator(device=dev).manual_seed(mb["seed"])
+    rnd = lambda s: torch.randn(P, device=dev, generator=gen) * s
+    theta, m, delta = rnd(mb["sigma"]), rnd(1e-3), torch.zeros(P, device=dev)
+    starts = [rnd(mb["sigma"]) for _ in range(G)]
+    works = [s + rnd(mb["drift_sigma"]) for s in starts]
+    lps = [torch.empty(P, dtype=torch.bfloat16, device=dev) for _ in range(G)]
+
+    def timed(fn, iters):
+        for i in range(2):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(iters):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    iters = max(args.steps, 20)
+    res = {}
+    # single events rotating over the 16 replicas so that nothing stays in the last-level cache
+    for label, N, t0, bpp in (("dn_event_nonboundary_N4", 4, 0, 24), ("dn_event_boundary_N4", 4, 3, 32),
+                              ("dn_event_N1_nesterov", 1, 0, 32), ("dn_event_nonboundary_N8", 8, 0, 24)):
+        ms = timed(lambda i: A.k_dn_group(theta, m, delta, [starts[i % G]], [works[i % G]], None, N, t0,
+                                          mb["outer_lr"], mb["outer_beta"]), iters)
+        res[label] = dict(ms=ms, bytes_per_param=bpp, GBps=P * bpp / ms / 1e6)
+    for g in mb["replicas"]:
+        bpp = 8 * g + 24 + 10 * g
+        ms = timed(lambda i: A.k_dn_group(theta, m, delta, starts[:g], works[:g], lps[:g], g, 0, mb["outer_lr"],
+                                          mb["outer_beta"], 0.0, restart=True), max(iters // 4, 5))
+        res[f"dn_group_G{g}_N{g}_restart"] = dict(ms=ms, bytes_per_param=bpp, GBps=P * bpp / ms / 1e6)
+    grad, am, av = rnd(1e-3), rnd(1e-3), rnd(1e-6).abs()
+    step = [0]
+
+    def adam(i):
+        step[0] += 1
+        A.k_adamw(works[i % G], grad, am, av, lps[i % G], P - 4096, step[0], 1e-3)
+    ms = timed(adam, iters)
+    res["adamw_fp32grad_bf16copy"] = dict(ms=ms, bytes_per_param=30, GBps=P * 30 / ms / 1e6)
+    key = "dn_event_nonboundary_N4"
+    out = dict(metric="DN/AdamW HBM GB/s", value=res[key]["GBps"], unit="GB/s", n_gpus=1, steps=iters, warmup=2,
+               ms_per_step=res[key]["ms"], higher_is_better=True, scaling="weak", vs_baseline=None, dtype="f32",
+               data="synthetic", config=dict(workload=f"outer_microbench: {P} fp32 parameters, 16 replicas resident, "
+                                                      "value = one non-boundary Delayed-Nesterov event (N=4, c=0)", results=res),
+               roofline=dict(bound="hbm", achieved=res[key]["GBps"], peak=PEAK_HBM_GBS, unit="GB/s",
+                             frac=res[key]["GBps"] / PEAK_HBM_GBS, traffic=None, kernel="dn_group_kernel<4>"),
+               cpu_baseline=None)
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -66,6 +129,9 @@ def main():
         print("bench.py: this build runs on ONE GPU (the simulated workers are replicas on HIP streams of "
               "a single MI355X); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.workload == "outer_microbench":
+        return outer_microbench(args)
 
     import numpy as np
     import torch
@@ -115,11 +181,15 @@ def main():
     run_events(0, args.warmup * N)
     ctx.sync()
     torch.cuda.synchronize()
+    # HIP events around every MFMA GEMM launch of the timed region, on the launching stream
+    A.prof_enable(True)
     t0 = time.perf_counter()
     tokens = run_events(args.warmup * N, n_events)
     ctx.sync()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    A.prof_enable(False)
+    prof = sorted(A.prof_collect(), key=lambda r: -r[2])
 
     tok_s = tokens / dt
     tflops = tok_s * flops_per_token(w) / 1e12
@@ -134,6 +204,15 @@ def main():
                            tokens_per_step=tokens // max(args.steps, 1),
                            model_tflops=tflops, mfma_frac_whole_path=tflops / PEAK_BF16_TFLOPS),
                roofline=None, cpu_baseline=None)
+    if prof:
+        # dominant kernel = the GEMM instantiation with the largest summed duration
+        name, launches, ms, fl = prof[0]
+        achieved = fl / (ms * 1e-3) / 1e12
+        out["roofline"] = dict(bound="mfma", achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                               frac=achieved / PEAK_BF16_TFLOPS, traffic=None, kernel=name, launches=launches,
+                               avg_us=1e3 * ms / launches, flops_per_launch=fl / launches,
+                               all_gemm_kernels=[dict(kernel=n, launches=l, avg_us=1e3 * m / l,
+                                                      tflops=f / (m * 1e-3) / 1e12) for n, l, m, f in prof])
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     ctx.close()

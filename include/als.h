@@ -174,6 +174,15 @@ int als_k_adamw(float* theta, const float* grad, float* m, float* v, void* bf16_
 int als_k_gemm(const void* A, const void* B, void* C, int M, int N, int K, int a_layout,
                int b_layout, int in_dtype, int out_dtype, int use_mfma, void* ws_dev,
                size_t ws_bytes, void* stream);
+/* Benchmark hooks.  als_prof_enable(1) makes every MFMA GEMM launch record a HIP event before
+ * and after itself on its own stream; als_prof_collect waits for the device and returns, per
+ * kernel instantiation (id), the number of launches, their summed duration in ms and their
+ * summed algorithmic FLOPs (2 M N K), then forgets them.  Returns the number of entries
+ * written (<= max_entries) or a negative error.  als_prof_kernel_name writes the kernel's
+ * template name for an id. */
+int als_prof_enable(int on);
+int als_prof_collect(int max_entries, int32_t* ids, int64_t* launches, double* ms, double* flops);
+int als_prof_kernel_name(int id, char* out, int out_len);
 /* Benchmark hook: force the MFMA GEMM tile to 256x256, 256x128 or 128x128 with nbuf = 2
  * (LDS double buffer) or 1 (single buffer, more workgroups per CU); 0,0,0 = automatic choice
  * by shape.  Process-wide, not thread-safe. */

@@ -87,6 +87,33 @@ lib.als_k_attention_fwd.argtypes = [_P, _P, _P, C.c_int, C.c_int, C.c_int, C.c_i
 lib.als_k_attention_bwd.argtypes = [_P, _P, _P, _P, _P, _P, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _P]
 
 
+lib.als_prof_enable.argtypes = [C.c_int]
+lib.als_prof_collect.argtypes = [C.c_int, _P, _P, _P, _P]
+lib.als_prof_kernel_name.argtypes = [C.c_int, C.c_char_p, C.c_int]
+lib.als_k_set_gemm_tile.argtypes = [C.c_int, C.c_int, C.c_int]
+
+
+def prof_enable(on: bool) -> None:
+    _check(lib.als_prof_enable(1 if on else 0))
+
+
+def prof_collect(max_entries: int = 64):
+    """[(kernel name, launches, total ms, total flops)] of the MFMA GEMM launches since enable."""
+    ids = np.zeros(max_entries, np.int32)
+    n_l = np.zeros(max_entries, np.int64)
+    ms = np.zeros(max_entries, np.float64)
+    fl = np.zeros(max_entries, np.float64)
+    n = lib.als_prof_collect(max_entries, _np_ptr(ids), _np_ptr(n_l), _np_ptr(ms), _np_ptr(fl))
+    if n < 0:
+        _check(n)
+    out = []
+    for i in range(n):
+        buf = C.create_string_buffer(160)
+        _check(lib.als_prof_kernel_name(int(ids[i]), buf, 160))
+        out.append((buf.value.decode(), int(n_l[i]), float(ms[i]), float(fl[i])))
+    return out
+
+
 def _check(rc: int) -> None:
     if rc != 0:
         raise AlsError(f"als error {rc}: {lib.als_last_error().decode()}")

@@ -40,8 +40,8 @@ void make_layout(const als_config& c, Layout* L);
 enum Epilogue {
   EPI_STORE = 0,   // C = acc
   EPI_RESID = 1,   // C(fp32) = R(fp32) + acc
-  EPI_GELU = 2,    // C = acc (pre-activation), C2 = gelu_tanh(acc)
-  EPI_DGELU = 3,   // C = acc * gelu_tanh'(U)
+  EPI_GELU = 2,    // C = gelu_tanh'(acc) (kept for the backward pass), C2 = gelu_tanh(acc)
+  EPI_DGELU = 3,   // C = acc * U, U = the saved gelu_tanh'(pre-activation)
 };
 
 struct GemmDesc {
@@ -55,7 +55,7 @@ struct GemmDesc {
   int epi;
   const float* R; int64_t ldr;       // EPI_RESID
   void* C2;                          // EPI_GELU second output (same type/ld as C)
-  const void* U;                     // EPI_DGELU pre-activation (operand type, ld = ldc)
+  const void* U;                     // EPI_DGELU saved derivative (operand type, ld = ldc)
   float* ws; size_t ws_bytes;        // scratch for split-K partials (may be null)
 };
 int gemm_generic(const GemmDesc& g, hipStream_t st);

@@ -78,9 +78,12 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmDesc g) {
       int64_t ci = (int64_t)gm * g.ldc + gn;
       float v = acc[i][j];
       if (EPI == EPI_RESID) v += g.R[(int64_t)gm * g.ldr + gn];
-      if (EPI == EPI_DGELU) v *= gelu_tanh_grad_f(ld<TI>(g.U, ci));
+      if (EPI == EPI_DGELU) v *= ld<TI>(g.U, ci);
+      if (EPI == EPI_GELU) {
+        reinterpret_cast<TO*>(g.C2)[ci] = (TO)gelu_tanh_f(v);
+        v = gelu_tanh_grad_f(v);
+      }
       reinterpret_cast<TO*>(g.C)[ci] = (TO)v;
-      if (EPI == EPI_GELU) reinterpret_cast<TO*>(g.C2)[ci] = (TO)gelu_tanh_f(v);
     }
   }
 }

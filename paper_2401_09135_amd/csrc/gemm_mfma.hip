@@ -17,12 +17,28 @@
 // LDS transpose load: in each group of 16 lanes, lane s supplies 4 consecutive bf16; lane r
 // receives element r%4 of lanes r/4, 4 + r/4, 8 + r/4, 12 + r/4.
 #include "common.h"
+#include <stdio.h>
+
+#include <mutex>
+#include <string>
+#include <vector>
 
 namespace als {
 
 namespace {
 
 constexpr int BK = 64;
+
+// ---- optional per-kernel timing (benchmarks): HIP events around every MFMA GEMM launch, on
+// the stream it is launched on, grouped by kernel instantiation -----------------------------
+struct ProfRec { hipEvent_t e0, e1; int id; double flops; };
+std::mutex g_prof_mu;
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof;
+
+int kernel_id(int bm, int bn, int al, int bl, int epi, int to_bf16, int split, int nbuf) {
+  return (bm / 128 - 1) | (bn / 128 - 1) << 1 | al << 2 | bl << 3 | epi << 4 | to_bf16 << 6 | split << 7 | (nbuf - 1) << 8;
+}
 
 template <int BM, int BN, int AL, int BL, int NBUF>
 struct Tile {
@@ -59,14 +75,14 @@ __device__ __forceinline__ float fast_tanh(float y) {
   float e = __builtin_amdgcn_exp2f(y * 2.8853900817779268f);  // e^{2y}
   return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + e);
 }
-__device__ __forceinline__ float gelu_f(float u) {
+// gelu_tanh(u) and its derivative from one tanh
+__device__ __forceinline__ void gelu_both(float u, float& val, float& grad) {
   const float a = 0.7978845608028654f, b = 0.044715f;
-  return 0.5f * u * (1.0f + fast_tanh(a * (u + b * u * u * u)));
-}
-__device__ __forceinline__ float gelu_grad_f(float u) {
-  const float a = 0.7978845608028654f, b = 0.044715f;
-  float th = fast_tanh(a * (u + b * u * u * u));
-  return 0.5f * (1.0f + th) + 0.5f * u * (1.0f - th * th) * a * (1.0f + 3.0f * b * u * u);
+  float u2 = u * u;
+  float th = fast_tanh(a * u * (1.0f + b * u2));
+  float hp = 0.5f * (1.0f + th);
+  val = u * hp;
+  grad = hp + 0.5f * u * (1.0f - th * th) * a * (1.0f + 3.0f * b * u2);
 }
 
 struct MfmaArgs {
@@ -236,24 +252,30 @@ __global__ __launch_bounds__(256, OCC) void gemm_mfma_kernel(MfmaArgs g) {
           f32x4 r = *reinterpret_cast<const f32x4*>(g.R + (int64_t)row * g.ldr + col);
           x += r;
         }
-        if (EPI == EPI_DGELU) {
+        if (EPI == EPI_DGELU) {  // U holds gelu'(pre-activation), saved by the forward pass
           bf16x4 u = *reinterpret_cast<const bf16x4*>(g.U + ci);
 #pragma unroll
-          for (int e = 0; e < 4; e++) x[e] *= gelu_grad_f((float)u[e]);
+          for (int e = 0; e < 4; e++) x[e] *= (float)u[e];
         }
         if (sizeof(TO) == 4) {
           *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(C) + ci) = x;
         } else {
           bf16x4 o;
-#pragma unroll
-          for (int e = 0; e < 4; e++) o[e] = (bf16)x[e];
-          *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16*>(C) + ci) = o;
-          if (EPI == EPI_GELU) {
+          if (EPI == EPI_GELU) {  // C <- gelu'(acc), C2 <- gelu(acc)
             bf16x4 o2;
 #pragma unroll
-            for (int e = 0; e < 4; e++) o2[e] = (bf16)gelu_f(x[e]);
+            for (int e = 0; e < 4; e++) {
+              float val, grad;
+              gelu_both(x[e], val, grad);
+              o[e] = (bf16)grad;
+              o2[e] = (bf16)val;
+            }
             *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16*>(g.C2) + ci) = o2;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; e++) o[e] = (bf16)x[e];
           }
+          *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16*>(C) + ci) = o;
         }
       }
   }
@@ -284,8 +306,25 @@ int launch(const MfmaArgs& a, int nsplit, hipStream_t st) {
     attr_set = true;
   }
   dim3 grid(a.tiles_m * a.tiles_n, 1, nsplit);
+  ProfRec rec;
+  bool prof = false;
+  if (g_prof_on) {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (g_prof_on && hipEventCreate(&rec.e0) == hipSuccess) {
+      if (hipEventCreate(&rec.e1) == hipSuccess) prof = true;
+      else (void)hipEventDestroy(rec.e0);
+    }
+  }
+  if (prof) ALS_HIP(hipEventRecord(rec.e0, st));
   hipLaunchKernelGGL(kern, grid, dim3(256), TL::LDS_BYTES, st, a);
   ALS_CHECK_LAUNCH();
+  if (prof) {
+    ALS_HIP(hipEventRecord(rec.e1, st));
+    rec.id = kernel_id(BM, BN, AL, BL, EPI, sizeof(TO) == 2, SPLIT, NBUF);
+    rec.flops = 2.0 * a.M * a.N * (double)a.K * nsplit;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    g_prof.push_back(rec);
+  }
   return ALS_OK;
 }
 
@@ -380,6 +419,49 @@ int gemm_mfma(const GemmDesc& g, hipStream_t st) {
 }
 
 }  // namespace als
+
+// Benchmark hooks: time every MFMA GEMM launch with HIP events on its own stream.
+extern "C" int als_prof_enable(int on) {
+  std::lock_guard<std::mutex> lk(als::g_prof_mu);
+  als::g_prof_on = on != 0;
+  return ALS_OK;
+}
+
+extern "C" int als_prof_collect(int max_entries, int32_t* ids, int64_t* launches, double* ms, double* flops) {
+  using namespace als;
+  if (max_entries < 0 || (max_entries > 0 && (!ids || !launches || !ms || !flops)))
+    return set_error(ALS_ERR_INVALID, "als_prof_collect: null output");
+  ALS_HIP(hipDeviceSynchronize());
+  std::lock_guard<std::mutex> lk(g_prof_mu);
+  int n = 0;
+  for (ProfRec& r : g_prof) {
+    float t = 0.0f;
+    bool ok = hipEventElapsedTime(&t, r.e0, r.e1) == hipSuccess;
+    (void)hipEventDestroy(r.e0);
+    (void)hipEventDestroy(r.e1);
+    if (!ok) continue;
+    int k = 0;
+    while (k < n && ids[k] != r.id) k++;
+    if (k == n) {
+      if (n == max_entries) continue;
+      ids[n] = r.id; launches[n] = 0; ms[n] = 0.0; flops[n] = 0.0;
+      n++;
+    }
+    launches[k] += 1; ms[k] += t; flops[k] += r.flops;
+  }
+  g_prof.clear();
+  return n;
+}
+
+extern "C" int als_prof_kernel_name(int id, char* out, int out_len) {
+  if (!out || out_len < 1) return als::set_error(ALS_ERR_INVALID, "als_prof_kernel_name: null output");
+  static const char* epi[4] = {"STORE", "RESID", "GELU", "DGELU"};
+  int nbuf = ((id >> 8) & 1) + 1, bm = ((id & 1) + 1) * 128, bn = (((id >> 1) & 1) + 1) * 128;
+  int occ = nbuf == 2 ? (bm == 128 ? 2 : 1) : (bm == 256 ? 2 : 3);
+  snprintf(out, out_len, "gemm_mfma_kernel<%d, %d, %d, %d, %s, %s, %s, %d, %d>", bm, bn, (id >> 2) & 1, (id >> 3) & 1,
+           epi[(id >> 4) & 3], (id >> 6) & 1 ? "bf16" : "float", (id >> 7) & 1 ? "true" : "false", nbuf, occ);
+  return ALS_OK;
+}
 
 // Tuning hook: force the MFMA GEMM tile (256x256, 256x128 or 128x128) and its LDS buffering
 // (2 = double, 1 = single buffer with more workgroups per CU); 0,0 restores the automatic choice.  Not thread-safe; meant for benchmarks.

@@ -210,3 +210,50 @@ def test_attention_mfma_matches_generic_kernel_closely():
     o2, _, l2, _, g2, _ = _attention_case(B, S, h, 64, torch.bfloat16, False)
     assert _rel(o1, o2) < 1e-2 and _rel(g1, g2) < 1.5e-2
     np.testing.assert_allclose(l1, l2, rtol=1e-4, atol=1e-4)
+
+
+@pytest.mark.timeout(900)
+def test_outer_step_microbench_vector_full_size():
+    """BASELINE configs[2]: 150M-element fp32 vector, 4 replicas, N = 4, one grouped pass ending
+    on the momentum update, and one AdamW step, all compared element by element."""
+    mb = I.OUTER_MICROBENCH
+    P, G, N = mb["P"], 4, 4
+    f = np.float32
+    theta = I.normal_vector(P, [mb["seed"], 1], mb["sigma"])
+    m = I.normal_vector(P, [mb["seed"], 2], 1e-3)
+    delta = np.zeros(P, f)
+    dn = DelayedNesterov(theta, mb["outer_lr"], mb["outer_beta"], N, 0.0)
+    dn.m[...] = m
+    th, md, dd = _dev(theta), _dev(m), _dev(delta)
+    ts, tw = [], []
+    for j in range(G):
+        start = I.normal_vector(P, [mb["seed"], 10 + j], mb["sigma"])
+        work = start + I.normal_vector(P, [mb["seed"], 30 + j], mb["drift_sigma"])
+        ts.append(_dev(start))
+        tw.append(_dev(work))
+        dn.event(start - work)
+        del start, work
+    A.k_dn_group(th, md, dd, ts, tw, None, N, 0, mb["outer_lr"], mb["outer_beta"], 0.0, restart=True)
+    torch.cuda.synchronize()
+    assert dn.t == 4 and not dn.delta.any()
+    assert _rel(th.cpu().numpy(), dn.theta) < 2e-6
+    np.testing.assert_allclose(md.cpu().numpy(), dn.m, rtol=1e-5, atol=1e-9)
+    assert not dd.any().item()
+    assert torch.equal(tw[3], th) and torch.equal(ts[0], th)
+    del ts, tw, dn
+    # AdamW on the same vector
+    g = I.normal_vector(P, [mb["seed"], 50], 1e-3)
+    ref = theta.copy()
+    opt = AdamW(P, f, wd=0.1, n_decayed=P - 4096)
+    opt.m[...] = m
+    opt.v[...] = m * m
+    opt.n = 6
+    am, av = _dev(m), _dev(m * m)
+    th2 = _dev(theta)
+    lp = torch.empty(P, dtype=torch.bfloat16, device=DEV)
+    A.k_adamw(th2, _dev(g), am, av, lp, P - 4096, 7, 1e-3)
+    opt.step(ref, g, 1e-3)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(th2.cpu().numpy(), ref, rtol=2e-6, atol=1e-9)
+    np.testing.assert_allclose(av.cpu().numpy(), opt.v, rtol=1e-5, atol=1e-15)
+    assert torch.equal(lp, th2.to(torch.bfloat16))

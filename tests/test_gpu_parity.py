@@ -64,7 +64,8 @@ def test_loss_and_gradient_one_batch(name, flags):
     assert _rel(g, rg) < (1.5e-2 if bf else 1e-5)
 
 
-@pytest.mark.parametrize("name,flags", [("tiny", 0), ("mini_f32", 0), ("mini_bf16", 1), ("mini_bf16", 0)])
+@pytest.mark.parametrize("name,flags", [("tiny", 0), ("mini_f32", 0), ("mini_bf16", 1), ("mini_bf16", 0),
+                                        ("mini_bf16_k16", 0)])
 def test_async_run_matches_oracle(name, flags):
     w = I.workload(name)
     theta0 = I.theta0(lm.param_layout(w), w["seed"])
@@ -147,3 +148,53 @@ def test_error_paths_return_codes():
         ctx.outer_apply_dn([9])
     assert ctx.worker_local_steps(0, tok[:0], 1e-3, want_losses=True).size == 0    # empty round
     ctx.close()
+
+
+@pytest.mark.timeout(900)
+def test_full_size_150m_architecture_one_sequence():
+    """Every kernel shape class of the 150M-class workload (d 896, 14 heads, V 32000, S 1024) on
+    one sequence: loss and gradient against the oracle."""
+    w = I.workload("lm150m_b1")
+    theta0 = I.theta0(lm.param_layout(w), w["seed"])
+    tok = _stream(w)(0).take(1)[0]
+    ctx = A.Context(A.Config.from_workload(w), theta0, n_streams=1)
+    loss, g = ctx.worker_loss_grad(0, torch.from_numpy(tok).to("cuda:0"))
+    ctx.close()
+    rloss, rg = lm.loss_and_grad(theta0.copy(), tok, w)
+    per = _per_tensor_rel(g, rg, w)
+    _record(f"loss_grad lm150m_b1: loss rel {abs(loss - rloss) / abs(rloss):.3e} grad rel-L2 {_rel(g, rg):.3e} "
+            f"worst tensor {max(per, key=per.get)} {max(per.values()):.3e}")
+    assert abs(loss - rloss) / abs(rloss) < TOL["bf16"]["loss"]
+    assert _rel(g, rg) < 1.5e-2 and max(per.values()) < 3e-2, per
+
+
+@pytest.mark.timeout(1500)
+def test_full_size_lm20m_step_in_bench_launch_configuration():
+    """BASELINE configs[1] at full size, launched as bench.py launches it (4 workers stepping
+    concurrently on 4 streams): worker 0's gradient, loss and first AdamW step against the
+    oracle; the other workers' first losses against oracle forward passes."""
+    w = I.workload("lm20m")
+    theta0 = I.theta0(lm.param_layout(w), w["seed"])
+    toks = [_stream(w)(i).take(1) for i in range(w["k"])]
+    ctx = A.Context(A.Config.from_workload(w), theta0)
+    dev = [torch.from_numpy(t).to("cuda:0") for t in toks]
+    loss0, g0 = ctx.worker_loss_grad(0, dev[0][0])
+    for i in range(w["k"]):
+        ctx.worker_local_steps(i, dev[i], w["lr"])
+    ctx.sync()
+    losses = [float(ctx.get_losses(i, 1)[0]) for i in range(w["k"])]
+    th_after = ctx.get_vector("worker_theta", 0)
+    ctx.close()
+    rloss, rg = lm.loss_and_grad(theta0.copy(), toks[0][0], w)
+    per = _per_tensor_rel(g0, rg, w)
+    _record(f"loss_grad lm20m full size: loss rel {abs(loss0 - rloss) / abs(rloss):.3e} grad rel-L2 {_rel(g0, rg):.3e} "
+            f"worst tensor {max(per, key=per.get)} {max(per.values()):.3e}")
+    assert abs(loss0 - rloss) / abs(rloss) < TOL["bf16"]["loss"]
+    assert abs(losses[0] - rloss) / abs(rloss) < TOL["bf16"]["loss"]
+    assert _rel(g0, rg) < 1.5e-2 and max(per.values()) < 3e-2, per
+    ref = theta0.copy()
+    AdamW(ref.size, np.float32, w["beta1"], w["beta2"], w["adam_eps"], w["wd"], lm.n_decayed(w)).step(ref, rg, w["lr"])
+    assert _rel(th_after, ref) < TOL["bf16"]["theta"]
+    for i in range(1, w["k"]):
+        ri = float(lm.forward(theta0, toks[i][0], w, keep=False)[0])
+        assert abs(losses[i] - ri) / abs(ri) < TOL["bf16"]["loss"], i
