@@ -174,6 +174,11 @@ int als_k_adamw(float* theta, const float* grad, float* m, float* v, void* bf16_
 int als_k_gemm(const void* A, const void* B, void* C, int M, int N, int K, int a_layout,
                int b_layout, int in_dtype, int out_dtype, int use_mfma, void* ws_dev,
                size_t ws_bytes, void* stream);
+/* Same with an epilogue: epi 0 store, 1 C(fp32) = R + A.B (R fp32 [M,N]), 2 C = gelu'(A.B) and
+ * C2 = gelu(A.B) (both bf16), 3 C = (A.B) * U (U bf16 [M,N]).  Unused pointers may be null. */
+int als_k_gemm_ex(const void* A, const void* B, void* C, int M, int N, int K, int a_layout,
+                  int b_layout, int in_dtype, int out_dtype, int use_mfma, int epi, const float* R,
+                  void* C2, const void* U, void* ws_dev, size_t ws_bytes, void* stream);
 /* Benchmark hooks.  als_prof_enable(1) makes every MFMA GEMM launch record a HIP event before
  * and after itself on its own stream; als_prof_collect waits for the device and returns, per
  * kernel instantiation (id), the number of launches, their summed duration in ms and their

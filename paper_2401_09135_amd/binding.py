@@ -276,6 +276,18 @@ def k_gemm(A, B, C_out, M, N, K, a_layout=0, b_layout=0, use_mfma=False, ws=None
                           ws.numel() * ws.element_size() if ws is not None else 0, _stream_handle(stream)))
 
 
+lib.als_k_gemm_ex.argtypes = [_P, _P, _P, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                              _P, _P, _P, _P, C.c_size_t, _P]
+
+
+def k_gemm_ex(A, B, C_out, M, N, K, a_layout=0, b_layout=0, use_mfma=False, epi=0, R=None, C2=None, U=None,
+              ws=None, stream=None):
+    p = lambda t: t.data_ptr() if t is not None else None
+    _check(lib.als_k_gemm_ex(A.data_ptr(), B.data_ptr(), C_out.data_ptr(), M, N, K, a_layout, b_layout, _dt(A),
+                             _dt(C_out), int(bool(use_mfma)), int(epi), p(R), p(C2), p(U), p(ws),
+                             ws.numel() * ws.element_size() if ws is not None else 0, _stream_handle(stream)))
+
+
 def k_attention_fwd(qkv, o, lse, B, S, h, dh, use_mfma=False, stream=None):
     _check(lib.als_k_attention_fwd(qkv.data_ptr(), o.data_ptr(), lse.data_ptr(), B, S, h, dh, _dt(qkv),
                                    int(bool(use_mfma)), _stream_handle(stream)))

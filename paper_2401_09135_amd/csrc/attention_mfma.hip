@@ -130,36 +130,47 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16* __restrict__ 
 #pragma unroll
         for (int kk = 0; kk < 4; kk++)
           s[kt] = MFMA(lds_direct(Ks + (kt * 32 + (lane & 31)) * ROW_D + kk * 32 + hf * 16), qf[kk], s[kt]);
+      // running maximum in raw score units; probabilities are exp2((s - m) * scale_log2) with
+      // the scale folded into one fma per element; masking only on tiles that cross the diagonal
       const bool need_mask = key0 + 63 > qw;
       float mx = -INFINITY;
+      if (need_mask) {
 #pragma unroll
-      for (int kt = 0; kt < 2; kt++)
+        for (int kt = 0; kt < 2; kt++)
 #pragma unroll
-        for (int v = 0; v < 16; v++) {
-          float x = s[kt][v] * scale_log2;
-          int key = key0 + kt * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-          if (need_mask && key > q) x = -INFINITY;
-          s[kt][v] = x;
-          mx = fmaxf(mx, x);
-        }
+          for (int v = 0; v < 16; v++) {
+            int key = key0 + kt * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+            if (key > q) s[kt][v] = -INFINITY;
+            mx = fmaxf(mx, s[kt][v]);
+          }
+      } else {
+#pragma unroll
+        for (int kt = 0; kt < 2; kt++)
+#pragma unroll
+          for (int v = 0; v < 16; v++) mx = fmaxf(mx, s[kt][v]);
+      }
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       const float m_new = fmaxf(m_run, mx);   // finite: key 0 is visible to every query
-      const float alpha = fast_exp2(m_run - m_new);
+      const float neg = -m_new * scale_log2;
       float lsum = 0.0f;
 #pragma unroll
       for (int kt = 0; kt < 2; kt++)
 #pragma unroll
         for (int v = 0; v < 16; v++) {
-          float p = fast_exp2(s[kt][v] - m_new);
+          float p = fast_exp2(fmaf(s[kt][v], scale_log2, neg));
           s[kt][v] = p;
           lsum += p;
         }
-      l_run = l_run * alpha + lsum;
-      m_run = m_new;
+      if (__any(m_new != m_run)) {  // wave-uniform: rescale only when some row's maximum moved
+        const float alpha = fast_exp2((m_run - m_new) * scale_log2);
+        l_run *= alpha;
 #pragma unroll
-      for (int dt = 0; dt < 2; dt++)
+        for (int dt = 0; dt < 2; dt++)
 #pragma unroll
-        for (int v = 0; v < 16; v++) oacc[dt][v] *= alpha;
+          for (int v = 0; v < 16; v++) oacc[dt][v] *= alpha;
+        m_run = m_new;
+      }
+      l_run += lsum;
 #pragma unroll
       for (int kt = 0; kt < 2; kt++)
 #pragma unroll
@@ -181,7 +192,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16* __restrict__ 
   }
   const float l = l_run + __shfl_xor(l_run, 32, 64);
   store_rows(o + ((int64_t)b * S + q) * d + hd * DH, oacc, 1.0f / l, hf);
-  if (hf == 0) lse[((int64_t)b * h + hd) * S + q] = (m_run + log2f(l)) * LN2;
+  if (hf == 0) lse[((int64_t)b * h + hd) * S + q] = (m_run * scale_log2 + log2f(l)) * LN2;
 }
 
 // D[b,h,q] = sum_c dO[q,c] O[q,c] : 8 lanes per (token, head)
@@ -259,12 +270,17 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16* __restrict
           s = MFMA(lds_direct(Ks + roff + kk * 32), qf[kk], s);
           dp = MFMA(lds_direct(Vs + roff + kk * 32), gf[kk], dp);
         }
+        if (need_mask) {
 #pragma unroll
-        for (int v = 0; v < 16; v++) {
-          int key = key0 + kt * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-          float p = fast_exp2(s[v] * scale_log2 - lse2);
-          if (need_mask && key > q) p = 0.0f;
-          s[v] = p * (dp[v] - Dq);
+          for (int v = 0; v < 16; v++) {
+            int key = key0 + kt * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+            float p = fast_exp2(fmaf(s[v], scale_log2, -lse2));
+            if (key > q) p = 0.0f;
+            s[v] = p * (dp[v] - Dq);
+          }
+        } else {
+#pragma unroll
+          for (int v = 0; v < 16; v++) s[v] = fast_exp2(fmaf(s[v], scale_log2, -lse2)) * (dp[v] - Dq);
         }
 #pragma unroll
         for (int kk = 0; kk < 2; kk++) {
@@ -351,6 +367,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16* __restric
       for (int g = 0; g < 4; g++) {
         l4[g] = *reinterpret_cast<const float4*>(lse_b + qs + 8 * g + 4 * hf);
         d4[g] = *reinterpret_cast<const float4*>(D_b + qs + 8 * g + 4 * hf);
+        l4[g].x *= -LOG2E; l4[g].y *= -LOG2E; l4[g].z *= -LOG2E; l4[g].w *= -LOG2E;
       }
       const int roff = (qh * 32 + (lane & 31)) * ROW_D + hf * 16;
       bf16x8 qa[4], ga[4];
@@ -383,9 +400,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16* __restric
         for (int v = 0; v < 16; v++) {
           const float lv = reinterpret_cast<const float*>(&l4[v >> 2])[v & 3];
           const float dvv = reinterpret_cast<const float*>(&d4[v >> 2])[v & 3];
-          int qi = qs + 8 * (v >> 2) + 4 * hf + (v & 3);
-          float p = fast_exp2(s[v] * scale_log2 - lv * LOG2E);
-          if (need_mask && key > qi) p = 0.0f;
+          float p = fast_exp2(fmaf(s[v], scale_log2, lv));
+          if (need_mask) {
+            int qi = qs + 8 * (v >> 2) + 4 * hf + (v & 3);
+            if (key > qi) p = 0.0f;
+          }
           s[v] = p;
           dp[v] = p * (dp[v] - dvv);
         }

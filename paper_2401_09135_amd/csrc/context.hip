@@ -508,6 +508,26 @@ extern "C" int als_k_gemm(const void* A, const void* B, void* C, int M, int N, i
   return gemm_generic(g, (hipStream_t)stream);
 }
 
+extern "C" int als_k_gemm_ex(const void* A, const void* B, void* C, int M, int N, int K, int a_layout,
+                             int b_layout, int in_dtype, int out_dtype, int use_mfma, int epi, const float* R,
+                             void* C2, const void* U, void* ws_dev, size_t ws_bytes, void* stream) {
+  if (!A || !B || !C) return set_error(ALS_ERR_INVALID, "null argument");
+  if (epi < 0 || epi > 3 || (epi == EPI_RESID && !R) || (epi == EPI_GELU && !C2) || (epi == EPI_DGELU && !U))
+    return set_error(ALS_ERR_INVALID, "epilogue %d lacks its operand", epi);
+  GemmDesc g;
+  memset(&g, 0, sizeof g);
+  g.A = A; g.B = B; g.C = C; g.M = M; g.N = N; g.K = K; g.a_layout = a_layout; g.b_layout = b_layout;
+  g.lda = a_layout == 0 ? K : M; g.ldb = b_layout == 0 ? N : K; g.ldc = N;
+  g.in_bf16 = in_dtype == ALS_DTYPE_BF16; g.c_bf16 = out_dtype == ALS_DTYPE_BF16; g.epi = epi;
+  g.R = R; g.ldr = N; g.C2 = C2; g.U = U;
+  g.ws = (float*)ws_dev; g.ws_bytes = ws_dev ? ws_bytes : 0;
+  if (use_mfma) {
+    if (!gemm_mfma_supported(g)) return set_error(ALS_ERR_INVALID, "shape/dtype/epilogue not supported by the MFMA GEMM");
+    return gemm_mfma(g, (hipStream_t)stream);
+  }
+  return gemm_generic(g, (hipStream_t)stream);
+}
+
 extern "C" int als_k_attention_fwd(const void* qkv, void* o, float* lse, int B, int S, int h, int dh,
                                    int dtype, int use_mfma, void* stream) {
   if (!qkv || !o || !lse) return set_error(ALS_ERR_INVALID, "null argument");

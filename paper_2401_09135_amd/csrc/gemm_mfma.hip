@@ -89,7 +89,7 @@ struct MfmaArgs {
   const bf16* A; const bf16* B;
   int64_t lda, ldb;
   int M, N, K;      // K = length of this launch's K range per split
-  int tiles_m, tiles_n;
+  int tiles_m, tiles_n, nsplit;
   void* C; int64_t ldc;
   const float* R; int64_t ldr;
   void* C2; const bf16* U;
@@ -107,14 +107,21 @@ __global__ __launch_bounds__(256, OCC) void gemm_mfma_kernel(MfmaArgs g) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
 
-  // Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of
-  // tiles (n fastest) so that tiles sharing an A panel share an L2.
+  // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Without split-K
+  // every XCD gets a contiguous run of tiles (n fastest), so tiles sharing an A panel share an
+  // L2.  With split-K the K slice is the fastest index: XCD x then owns the slices z = x mod 8
+  // for ALL output tiles, and each slice of both operands is fetched from HBM once.
   int ntiles = g.tiles_m * g.tiles_n;
-  int id = blockIdx.x;
-  int per = ntiles / 8;
-  int tile = (id < per * 8) ? (id % 8) * per + id / 8 : id;
+  int id = blockIdx.x, tile, zsplit = 0;
+  if (SPLIT) {
+    zsplit = id % g.nsplit;
+    tile = id / g.nsplit;
+  } else {
+    int per = ntiles / 8;
+    tile = (id < per * 8) ? (id % 8) * per + id / 8 : id;
+  }
   const int m0 = (tile / g.tiles_n) * BM, n0 = (tile % g.tiles_n) * BN;
-  const int64_t kbase = (int64_t)blockIdx.z * g.K;
+  const int64_t kbase = (int64_t)zsplit * g.K;
 
   const bf16* Ag = AL == 0 ? g.A + (int64_t)m0 * g.lda + kbase : g.A + kbase * g.lda + m0;
   const bf16* Bg = BL == 1 ? g.B + (int64_t)n0 * g.ldb + kbase : g.B + kbase * g.ldb + n0;
@@ -237,7 +244,7 @@ __global__ __launch_bounds__(256, OCC) void gemm_mfma_kernel(MfmaArgs g) {
 
   // epilogue: 4 consecutive columns per lane and access
   TO* C = reinterpret_cast<TO*>(g.C);
-  if (SPLIT) C += (int64_t)blockIdx.z * g.split_stride;
+  if (SPLIT) C += (int64_t)zsplit * g.split_stride;
 #pragma unroll
   for (int i = 0; i < TM; i++) {
     const int row = m0 + wm * WM + i * 32 + (lane & 31);
@@ -305,7 +312,7 @@ int launch(const MfmaArgs& a, int nsplit, hipStream_t st) {
                                 hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES));
     attr_set = true;
   }
-  dim3 grid(a.tiles_m * a.tiles_n, 1, nsplit);
+  dim3 grid(a.tiles_m * a.tiles_n * nsplit);
   ProfRec rec;
   bool prof = false;
   if (g_prof_on) {
@@ -376,25 +383,27 @@ static int g_force_bm = 0, g_force_bn = 0, g_force_nbuf = 0;  // tuning override
 
 int gemm_mfma(const GemmDesc& g, hipStream_t st) {
   if (!gemm_mfma_supported(g)) return set_error(ALS_ERR_INVALID, "gemm_mfma: unsupported shape or layout");
-  // Tile choice (measured on MI355X): the single-buffered variants, which put 2-3 workgroups
-  // on a CU so that one's prologue/epilogue hides behind another's MFMAs, win on this path's
-  // shapes (short K, M or N large); 256x128 when that still leaves two tiles per CU.
+  // Tile choice (measured on MI355X with the real epilogues): the single-buffered 128x128
+  // variant, 3 workgroups per CU so that one's prologue/epilogue hides behind another's MFMAs,
+  // wins on this path's shapes (short K, tall M); 256x128 only for very wide outputs (the LM
+  // head and its weight gradient).
   int bm = 128, bn = 128, nbuf = 1;
-  const int target = 256;
   if (g_force_bm && fits(g.M, g.N, g_force_bm, g_force_bn)) { bm = g_force_bm; bn = g_force_bn; nbuf = g_force_nbuf; }
-  else if (g.a_layout == 1) { nbuf = 2; }
-  else if (fits(g.M, g.N, 256, 128) && (g.M / 256) * (g.N / 128) >= 2 * target) { bm = 256; bn = 128; }
+  else if (g.a_layout == 1) {
+    if (fits(g.M, g.N, 256, 128) && (g.M / 256) * (g.N / 128) >= 128) { bm = 256; bn = 128; nbuf = 1; }
+    else nbuf = 2;
+  } else if (fits(g.M, g.N, 256, 128) && (g.M / 256) * (g.N / 128) >= 2048) { bm = 256; bn = 128; }
   MfmaArgs a;
   a.A = (const bf16*)g.A; a.B = (const bf16*)g.B; a.lda = g.lda; a.ldb = g.ldb;
   a.M = g.M; a.N = g.N; a.K = g.K; a.tiles_m = g.M / bm; a.tiles_n = g.N / bn;
   a.C = g.C; a.ldc = g.ldc; a.R = g.R; a.ldr = g.ldr; a.C2 = g.C2; a.U = (const bf16*)g.U;
-  a.split_stride = 0;
+  a.split_stride = 0; a.nsplit = 1;
   int nsplit = 1;
   if (g.a_layout == 1 && g.b_layout == 0 && g.ldc == g.N) {
     // weight-gradient shape: few tiles, long K.  Split K so the grid covers the chip, as far
     // as the workspace allows; each split keeps at least 512 of K.
     int tiles = a.tiles_m * a.tiles_n;
-    int want = (2 * target + tiles - 1) / tiles;
+    int want = (512 + tiles - 1) / tiles;  // about two workgroups per CU
     int maxk = g.K / 512;
     size_t per = (size_t)g.M * g.N * sizeof(float);
     int maxws = g.ws ? (int)(g.ws_bytes / per) : 1;
@@ -404,7 +413,7 @@ int gemm_mfma(const GemmDesc& g, hipStream_t st) {
     while (nsplit > 1 && (g.K % (nsplit * BK))) nsplit--;
   }
   if (nsplit > 1) {
-    a.K = g.K / nsplit;
+    a.K = g.K / nsplit; a.nsplit = nsplit;
     a.C = g.ws; a.ldc = g.N; a.split_stride = (int64_t)g.M * g.N;
     int rc = dispatch(g, a, bm, bn, nbuf, nsplit, st);
     if (rc) return rc;

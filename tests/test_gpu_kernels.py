@@ -257,3 +257,50 @@ def test_outer_step_microbench_vector_full_size():
     np.testing.assert_allclose(th2.cpu().numpy(), ref, rtol=2e-6, atol=1e-9)
     np.testing.assert_allclose(av.cpu().numpy(), opt.v, rtol=1e-5, atol=1e-15)
     assert torch.equal(lp, th2.to(torch.bfloat16))
+
+
+@pytest.mark.parametrize("mfma", [False, True])
+def test_gemm_epilogues(mfma):
+    M, N, K = 256, 384, 128
+    rng = np.random.default_rng(0)
+    a = _dev(rng.standard_normal((M, K)).astype(np.float32), torch.bfloat16)
+    w = _dev(rng.standard_normal((K, N)).astype(np.float32) * 0.2, torch.bfloat16)
+    acc = a.float().cpu().numpy().astype(np.float64) @ w.float().cpu().numpy().astype(np.float64)
+    # residual
+    r = _dev(rng.standard_normal((M, N)).astype(np.float32))
+    c = torch.empty(M, N, dtype=torch.float32, device=DEV)
+    A.k_gemm_ex(a, w, c, M, N, K, 0, 0, mfma, epi=1, R=r)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(c.cpu().numpy(), acc + r.cpu().numpy(), rtol=1e-4, atol=1e-3)
+    # GELU pair: C = gelu'(acc), C2 = gelu(acc)
+    gp = torch.empty(M, N, dtype=torch.bfloat16, device=DEV)
+    gv = torch.empty(M, N, dtype=torch.bfloat16, device=DEV)
+    A.k_gemm_ex(a, w, gp, M, N, K, 0, 0, mfma, epi=2, C2=gv)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(gv.float().cpu().numpy(), lm.gelu_fwd(acc), rtol=1e-2, atol=1e-2)
+    np.testing.assert_allclose(gp.float().cpu().numpy(), lm.gelu_grad(acc), rtol=1e-2, atol=1e-2)
+    # multiply by a saved derivative (input-gradient layout: B stored [N, K])
+    u = _dev(rng.standard_normal((M, N)).astype(np.float32), torch.bfloat16)
+    wt = w.t().contiguous()
+    d = torch.empty(M, N, dtype=torch.bfloat16, device=DEV)
+    A.k_gemm_ex(a, wt, d, M, N, K, 0, 1, mfma, epi=3, U=u)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(d.float().cpu().numpy(), acc * u.float().cpu().numpy(), rtol=1e-2, atol=2e-2)
+
+
+def test_gemm_mfma_tile_variants_agree():
+    """Every tile / buffering variant of the MFMA GEMM gives the same product."""
+    M, N, K = 512, 512, 256
+    rng = np.random.default_rng(1)
+    a = _dev(rng.standard_normal((M, K)).astype(np.float32), torch.bfloat16)
+    b = _dev(rng.standard_normal((K, N)).astype(np.float32), torch.bfloat16)
+    ref = a.float().cpu().numpy().astype(np.float64) @ b.float().cpu().numpy().astype(np.float64)
+    try:
+        for tile in [(256, 256, 2), (256, 128, 2), (256, 128, 1), (128, 128, 2), (128, 128, 1)]:
+            A.lib.als_k_set_gemm_tile(*tile)
+            c = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
+            A.k_gemm(a, b, c, M, N, K, 0, 0, use_mfma=True)
+            torch.cuda.synchronize()
+            np.testing.assert_allclose(c.cpu().numpy(), ref, rtol=1e-4, atol=2e-3, err_msg=str(tile))
+    finally:
+        A.lib.als_k_set_gemm_tile(0, 0, 0)
