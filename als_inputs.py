@@ -46,6 +46,11 @@ WORKLOADS = {
     # 16 heterogeneous workers (BASELINE configs[4]'s scheduling shape) on the reduced model
     "mini_bf16_k16": dict(_COMMON, L=2, d=256, h=4, ff=1024, V=1024, S=128, B=2, dtype="bf16",
                           k=16, speeds=("uniform", 1.0, 4.0), H=6, N=16, n_events=16),
+    # grace period > 0 and momentum activation c > 0 (the paper's ablation knobs), fp32 and bf16
+    "tiny_grace_c": dict(_COMMON, L=2, d=64, h=2, ff=256, V=256, S=32, B=8, dtype="f32", k=4,
+                         speeds=[1.0, 1.5, 2.0, 3.0], H=5, N=4, n_events=12, tau_grace=0.2, dn_c=0.1),
+    "mini_bf16_grace_c": dict(_COMMON, L=2, d=256, h=4, ff=1024, V=1024, S=128, B=4, dtype="bf16",
+                              k=4, speeds=[1.0, 1.2, 1.6, 2.4], H=10, N=4, n_events=8, tau_grace=0.5, dn_c=0.25),
     "mini_f32": dict(_COMMON, L=2, d=128, h=4, ff=384, V=320, S=48, B=3, dtype="f32",
                      k=3, speeds=[1.0, 2.0, 2.0], H=4, N=3, n_events=6),
 }

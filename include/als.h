@@ -128,6 +128,21 @@ int als_outer_apply_dn(als_ctx* ctx, const int32_t* workers, int n_group, int re
 int als_dylu_schedule(const double* speeds, int k, int H_max, double tau_grace, int n_events,
                       int32_t* H_out, int32_t* ev_worker, double* ev_time, int32_t* ev_group_end);
 
+/* Bookkeeping of train() (appendix pseudocode), host only.
+ * als_lr_schedule: Eq. (lr) for the n consecutive steps t0 .. t0+n-1 of one data shard: linear
+ *   warm-up t * eta_max / t_warmup while t < t_warmup, then eta_min + (eta_max - eta_min) / 2 *
+ *   (1 + cos(pi * ratio)), ratio = (t - t_warmup) / max(T - t_warmup, 0) clamped to [0, 1] (1 if
+ *   the denominator is 0).  Computed in fp64, written as float into lr_out[n] (the lr_host
+ *   argument of als_worker_local_steps).  Errors: negative counts, eta_min < 0, eta_max < eta_min.
+ * als_shard_sample: Eq. (data_sample): p_i proportional to max(sizes_i / sum sizes - learned_i /
+ *   sum learned, 0) (progress share 0 while nothing is learned; the size shares if no shard is
+ *   behind); writes p into p_out[k] (nullable) and the shard chosen by inverse CDF from the
+ *   caller's uniform number u in [0, 1) into *shard_out (nullable). */
+int als_lr_schedule(int64_t t0, int n, int64_t t_warmup, int64_t T, double eta_max, double eta_min,
+                    float* lr_out);
+int als_shard_sample(const double* sizes, const double* learned, int k, double u, double* p_out,
+                     int32_t* shard_out);
+
 /* ---- helpers for tests and drivers -------------------------------------------------- */
 #define ALS_VEC_THETA 0        /* server parameters              (worker ignored) */
 #define ALS_VEC_MOMENTUM 1     /* server momentum m              (worker ignored) */

@@ -153,6 +153,28 @@ def dylu_schedule(speeds, H_max: int, tau_grace: float = 0.0, n_events: int = 0)
     return H[:k], ew[:n_events], et[:n_events], eg[:n_events]
 
 
+lib.als_lr_schedule.argtypes = [C.c_int64, C.c_int, C.c_int64, C.c_int64, C.c_double, C.c_double, _P]
+lib.als_shard_sample.argtypes = [_P, _P, C.c_int, C.c_double, _P, _P]
+
+
+def lr_schedule(t0: int, n: int, t_warmup: int, T: int, eta_max: float, eta_min: float) -> np.ndarray:
+    out = np.zeros(max(n, 1), dtype=np.float32)
+    _check(lib.als_lr_schedule(int(t0), int(n), int(t_warmup), int(T), float(eta_max), float(eta_min), _np_ptr(out)))
+    return out[:n]
+
+
+def shard_sample(sizes, learned, u: float):
+    """Returns (probabilities[k], chosen shard)."""
+    s = np.ascontiguousarray(sizes, dtype=np.float64)
+    n = np.ascontiguousarray(learned, dtype=np.float64)
+    if s.shape != n.shape:
+        raise AlsError("sizes and learned must have the same length")
+    p = np.zeros(max(s.size, 1), dtype=np.float64)
+    pick = np.zeros(1, dtype=np.int32)
+    _check(lib.als_shard_sample(_np_ptr(s), _np_ptr(n), int(s.size), float(u), _np_ptr(p), _np_ptr(pick)))
+    return p[:s.size], int(pick[0])
+
+
 def _stream_handle(stream) -> int:
     return 0 if stream is None else int(stream.cuda_stream)
 

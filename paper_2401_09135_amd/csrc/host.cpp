@@ -159,3 +159,67 @@ extern "C" int als_dylu_schedule(const double* speeds, int k, int H_max, double 
   }
   return ALS_OK;
 }
+
+// Eq. (lr): linear warm-up, then cosine decay to eta_min, per data shard.  ratio = (t - t_warmup)
+// / max(T - t_warmup, 0) clamped to [0, 1]; a zero denominator gives ratio 1.
+extern "C" int als_lr_schedule(int64_t t0, int n, int64_t t_warmup, int64_t T, double eta_max, double eta_min,
+                               float* lr_out) {
+  if (n < 0 || t0 < 0 || t_warmup < 0 || T < 0) return set_error(ALS_ERR_INVALID, "als_lr_schedule: negative argument");
+  if (n > 0 && !lr_out) return set_error(ALS_ERR_INVALID, "als_lr_schedule: lr_out is null");
+  if (!isfinite(eta_max) || !isfinite(eta_min) || eta_min < 0 || eta_max < eta_min)
+    return set_error(ALS_ERR_INVALID, "als_lr_schedule: need 0 <= eta_min <= eta_max, finite");
+  const double pi = 3.14159265358979323846;
+  for (int i = 0; i < n; i++) {
+    int64_t t = t0 + i;
+    double lr;
+    if (t < t_warmup) {
+      lr = (double)t * eta_max / (double)t_warmup;
+    } else {
+      int64_t denom = T - t_warmup > 0 ? T - t_warmup : 0;
+      double ratio = denom == 0 ? 1.0 : (double)(t - t_warmup) / (double)denom;
+      if (ratio < 0.0) ratio = 0.0;
+      if (ratio > 1.0) ratio = 1.0;
+      lr = eta_min + 0.5 * (eta_max - eta_min) * (1.0 + cos(ratio * pi));
+    }
+    lr_out[i] = (float)lr;
+  }
+  return ALS_OK;
+}
+
+// Eq. (data_sample): p_i proportional to max(|D_i| / sum |D_j| - n_i / sum n_j, 0); the progress
+// share is 0 while nothing has been learned; if no shard is behind, the size shares are used.
+// The shard is drawn by inverse CDF from the caller's uniform number u in [0, 1).
+extern "C" int als_shard_sample(const double* sizes, const double* learned, int k, double u, double* p_out,
+                                int32_t* shard_out) {
+  if (!sizes || !learned || k < 1) return set_error(ALS_ERR_INVALID, "als_shard_sample: null argument or k < 1");
+  if (!(u >= 0.0 && u < 1.0)) return set_error(ALS_ERR_INVALID, "als_shard_sample: u must lie in [0, 1)");
+  double ssum = 0.0, nsum = 0.0;
+  for (int i = 0; i < k; i++) {
+    if (!(sizes[i] > 0) || !isfinite(sizes[i]) || !(learned[i] >= 0) || !isfinite(learned[i]))
+      return set_error(ALS_ERR_INVALID, "als_shard_sample: sizes must be positive, learned non-negative");
+    ssum += sizes[i];
+    nsum += learned[i];
+  }
+  std::vector<double> w(k);
+  double wsum = 0.0;
+  for (int i = 0; i < k; i++) {
+    double d = sizes[i] / ssum - (nsum > 0 ? learned[i] / nsum : 0.0);
+    w[i] = d > 0 ? d : 0.0;
+    wsum += w[i];
+  }
+  if (!(wsum > 0.0)) {
+    wsum = 0.0;
+    for (int i = 0; i < k; i++) { w[i] = sizes[i] / ssum; wsum += w[i]; }
+  }
+  int pick = -1, last_pos = 0;
+  double c = 0.0;
+  for (int i = 0; i < k; i++) {
+    double p = w[i] / wsum;
+    if (p_out) p_out[i] = p;
+    if (p > 0) last_pos = i;
+    c += p;
+    if (pick < 0 && u < c) pick = i;
+  }
+  if (shard_out) *shard_out = pick >= 0 ? pick : last_pos;
+  return ALS_OK;
+}

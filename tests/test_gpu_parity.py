@@ -65,7 +65,7 @@ def test_loss_and_gradient_one_batch(name, flags):
 
 
 @pytest.mark.parametrize("name,flags", [("tiny", 0), ("mini_f32", 0), ("mini_bf16", 1), ("mini_bf16", 0),
-                                        ("mini_bf16_k16", 0)])
+                                        ("mini_bf16_k16", 0), ("tiny_grace_c", 0), ("mini_bf16_grace_c", 0)])
 def test_async_run_matches_oracle(name, flags):
     w = I.workload(name)
     theta0 = I.theta0(lm.param_layout(w), w["seed"])
@@ -198,3 +198,20 @@ def test_full_size_lm20m_step_in_bench_launch_configuration():
     for i in range(1, w["k"]):
         ri = float(lm.forward(theta0, toks[i][0], w, keep=False)[0])
         assert abs(losses[i] - ri) / abs(ri) < TOL["bf16"]["loss"], i
+
+
+def test_per_step_learning_rate_schedule_feeds_local_steps():
+    """Eq. (lr) values from the library's schedule helper drive the per-step lr array."""
+    w = I.workload("tiny")
+    theta0 = I.theta0(lm.param_layout(w), 0)
+    lrs = A.lr_schedule(0, 5, 3, 5, 2e-3, 1e-5)           # 3 warm-up steps, then cosine to eta_min
+    assert lrs[0] == 0.0 and lrs[3] == np.float32(2e-3)
+    st = _stream(w)
+    ctx = A.Context(A.Config.from_workload(w), theta0, n_streams=1)
+    losses = ctx.worker_local_steps(0, torch.from_numpy(st(0).take(5)).to("cuda:0"), lrs, want_losses=True)
+    got = ctx.get_vector("worker_theta", 0)
+    ctx.close()
+    wk = run.Worker(0, theta0, w, st(0), np.float32)
+    wk.local_steps(5, w, lrs=[float(x) for x in lrs])
+    np.testing.assert_allclose(losses, wk.losses, rtol=1e-5)
+    assert _rel(got, wk.theta) < 1e-5
