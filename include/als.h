@@ -116,6 +116,30 @@ int als_worker_local_steps(als_ctx* ctx, int worker, int n_steps, const int32_t*
  * the restarts.  Ordered after the listed workers' pending local steps. */
 int als_outer_apply_dn(als_ctx* ctx, const int32_t* workers, int n_group, int restart_flag);
 
+/* The comparison rules of the paper's "Existing Fixes" paragraph on the same fused pass.
+ *   kind ALS_RULE_DN: Alg. 3 as in als_outer_apply_dn (N = 1 gives asynchronous DiLoCo).
+ *   kind ALS_RULE_BUFFER: "Async. Buffer": pseudo-gradients are only added to Delta; every N-th
+ *     event applies one Nesterov step (Eq. nesterov) on Delta/N and clears Delta.
+ *   poly_exponent a > 0: "Poly": each pseudo-gradient is scaled by (1 + staleness)^-a, staleness =
+ *     server events applied since that worker's replica (re)started (the paper uses a = 0.5).
+ *   staleness_threshold >= 0: "PolyThres": a worker whose staleness exceeds it is discarded (no
+ *     server change, no event counted) but still restarts; -1 = never.
+ *   dc_lambda > 0: "Delay Comp.": g <- g + lambda g*g*(theta_now - theta_at_worker_start),
+ *     elementwise, before any discount.
+ * Everything else (ordering, restart, errors) as als_outer_apply_dn. */
+#define ALS_RULE_DN 0
+#define ALS_RULE_BUFFER 1
+typedef struct als_outer_rule {
+  int32_t kind;
+  int32_t staleness_threshold;
+  double poly_exponent;
+  double dc_lambda;
+} als_outer_rule;
+int als_outer_apply_rule(als_ctx* ctx, const int32_t* workers, int n_group, int restart_flag,
+                         const als_outer_rule* rule);
+/* Server events applied since the worker's replica (re)started, or -1 on a bad argument. */
+int64_t als_worker_staleness(als_ctx* ctx, int worker);
+
 /* Eq. (DyLU) and, optionally, the event order of Alg. 2 on the simulated clock.  Host only.
  *   H_out[k] = max(1, floor(speeds[i] / max(speeds) * H_max)) in fp64.
  *   If ev_worker is non-null, also writes the first n_events sync events: worker index,

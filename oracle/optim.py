@@ -79,6 +79,42 @@ class DelayedNesterov:
         return self.theta
 
 
+# ---- the comparison rules of the "Existing Fixes" paragraph (Optimization Challenge section) ----
+def poly_weight(staleness, exponent=0.5):
+    """Async. DiLoCo + Poly: g <- (1 + staleness)^-0.5 g."""
+    return (1.0 + float(staleness)) ** (-exponent)
+
+
+def delay_compensated(g, theta_now, theta_then, lam):
+    """Async. DiLoCo + Delay Comp.: first-order correction of a stale pseudo-gradient with the
+    diagonal outer-product approximation of the Hessian, g + lam * g*g*(theta_now - theta_then)."""
+    t = g.dtype.type
+    return g + t(lam) * g * g * (theta_now - theta_then)
+
+
+class AsyncBuffer:
+    """Async. Buffer: pseudo-gradients are accumulated first-in first-out; every N-th one the
+    average is applied with one Nesterov step (Eq. nesterov); parameters do not move in between."""
+
+    def __init__(self, theta0, lr, beta, N):
+        self.theta = theta0.copy()
+        self.m = np.zeros_like(theta0)
+        self.delta = np.zeros_like(theta0)
+        self.t = 0
+        self.lr, self.beta, self.N = lr, beta, int(N)
+
+    def event(self, g):
+        f = self.theta.dtype.type
+        self.delta += g
+        if (self.t + 1) % self.N == 0:
+            gbar = self.delta / f(self.N)
+            self.m = f(self.beta) * self.m + gbar
+            self.theta = self.theta - f(self.lr) * (f(self.beta) * self.m + gbar)
+            self.delta = np.zeros_like(self.delta)
+        self.t += 1
+        return self.theta
+
+
 def dylu_steps(speeds, H):
     """Eq. (DyLU): floor(v_i / max v * H), evaluated in fp64 in that order; a result of 0
     is raised to 1 (a zero-step job would return a zero pseudo-gradient in zero time)."""

@@ -7,7 +7,8 @@ from __future__ import annotations
 import numpy as np
 
 from . import lm
-from .optim import AdamW, DelayedNesterov, dylu_steps, nesterov_step, pseudo_gradient
+from .optim import (AdamW, AsyncBuffer, DelayedNesterov, delay_compensated, dylu_steps, nesterov_step,
+                    poly_weight, pseudo_gradient)
 from .scheduler import event_trace
 
 
@@ -34,31 +35,56 @@ class Worker:
             self.losses.append(float(loss))
 
 
-def run_async(cfg, theta0, make_stream, dtype=np.float32, n_events=None, log=None):
-    """Returns dict(theta, m, delta, t, losses[k][...], steps, groups, workers)."""
+def run_async(cfg, theta0, make_stream, dtype=np.float32, n_events=None, log=None, rule=None):
+    """Returns dict(theta, m, delta, t, losses[k][...], steps, groups, workers).
+
+    rule (optional) selects one of the paper's comparison methods on top of the same loop:
+      dict(kind="buffer")                         Async. Buffer with the configured N
+      dict(poly_exponent=0.5)                     Async. DiLoCo + Poly
+      dict(poly_exponent=0.5, staleness_threshold=10)   ... + PolyThres (stale updates dropped)
+      dict(dc_lambda=lam)                         Async. DiLoCo + Delay Comp.
+    Staleness of an update = server events applied since its worker (re)started."""
     theta0 = theta0.astype(dtype)
     k = cfg["k"]
     steps = dylu_steps(cfg["speeds"], cfg["H"])
     n_events = cfg["n_events"] if n_events is None else n_events
     groups = event_trace(cfg["speeds"], steps, cfg["tau_grace"], n_events)
-    server = DelayedNesterov(theta0, cfg["outer_lr"], cfg["outer_beta"], cfg["N"], cfg["dn_c"])
+    rule = rule or {}
+    if rule.get("kind") == "buffer":
+        server = AsyncBuffer(theta0, cfg["outer_lr"], cfg["outer_beta"], cfg["N"])
+    else:
+        server = DelayedNesterov(theta0, cfg["outer_lr"], cfg["outer_beta"], cfg["N"], cfg["dn_c"])
     workers = [Worker(i, theta0, cfg, make_stream(i), dtype) for i in range(k)]
+    t_restart = [0] * k
+    stale_log = []
     for w in workers:                       # train(W, theta) before the loop
         w.local_steps(int(steps[w.idx]), cfg)
     for g in groups:
         for (wi, _t) in g["events"]:
             w = workers[wi]
-            server.event(pseudo_gradient(w.theta_start, w.theta))
+            stale = server.t - t_restart[wi]
+            stale_log.append(stale)
+            thr = rule.get("staleness_threshold", -1)
+            if thr >= 0 and stale > thr:
+                continue                         # PolyThres: the update is dropped
+            pg = pseudo_gradient(w.theta_start, w.theta)
+            if rule.get("dc_lambda", 0.0):
+                pg = delay_compensated(pg, server.theta, w.theta_start, rule["dc_lambda"])
+            if rule.get("poly_exponent", 0.0):
+                pg = pg * dtype(poly_weight(stale, rule["poly_exponent"]))
+            server.event(pg)
             if log is not None:
                 log(server, wi)
         if g["complete"]:                   # train(W_completed, theta)
             for (wi, _t) in g["events"]:
                 workers[wi].restart(server.theta)
+                t_restart[wi] = server.t
             if g is not groups[-1]:
                 for (wi, _t) in g["events"]:
                     workers[wi].local_steps(int(steps[wi]), cfg)
     return dict(theta=server.theta, m=server.m, delta=server.delta, t=server.t,
-                losses=[w.losses for w in workers], steps=steps, groups=groups, workers=workers)
+                losses=[w.losses for w in workers], steps=steps, groups=groups, workers=workers,
+                staleness=stale_log)
 
 
 def run_diloco_sync(cfg, theta0, make_stream, n_outer, H, dtype=np.float32):

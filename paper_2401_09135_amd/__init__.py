@@ -4,11 +4,11 @@ The binding only marshals arguments (ctypes) and uses torch for device memory an
 every step of the path runs inside the library's HIP kernels.  Importing this package fails
 loudly if the library has not been built (``python -m paper_2401_09135_amd.build``).
 """
-from .binding import (ALS_DTYPE_BF16, ALS_DTYPE_F32, AlsError, Config, Context, VEC, dylu_schedule,
+from .binding import (RULE_BUFFER, RULE_DN, OuterRule, ALS_DTYPE_BF16, ALS_DTYPE_F32, AlsError, Config, Context, VEC, dylu_schedule,
                       k_adamw, k_attention_bwd, k_attention_fwd, k_dn_group, k_gemm, k_gemm_ex, lib, lr_schedule, shard_sample, lib_path,
                       param_count, param_count_decayed, param_offsets, prof_collect, prof_enable)
 from .driver import run_async
 
-__all__ = ["ALS_DTYPE_BF16", "ALS_DTYPE_F32", "AlsError", "Config", "Context", "VEC",
+__all__ = ["RULE_BUFFER", "RULE_DN", "OuterRule", "ALS_DTYPE_BF16", "ALS_DTYPE_F32", "AlsError", "Config", "Context", "VEC",
            "dylu_schedule", "k_adamw", "k_attention_bwd", "k_attention_fwd", "k_dn_group", "k_gemm",
            "lib", "lib_path", "param_count", "param_count_decayed", "param_offsets", "prof_collect", "prof_enable", "run_async"]

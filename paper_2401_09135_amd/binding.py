@@ -54,6 +54,12 @@ class Config(C.Structure):
                    dn_c=w["dn_c"], norm_eps=w["norm_eps"])
 
 
+class OuterRule(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("staleness_threshold", C.c_int32), ("poly_exponent", C.c_double),
+                ("dc_lambda", C.c_double)]
+
+
+RULE_DN, RULE_BUFFER = 0, 1
 _P = C.c_void_p
 lib.als_last_error.restype = C.c_char_p
 lib.als_param_count.restype = C.c_int64
@@ -67,6 +73,9 @@ lib.als_init.argtypes = [C.POINTER(Config), _P, C.c_size_t, _P, C.POINTER(_P), C
 lib.als_destroy.argtypes = [_P]
 lib.als_worker_local_steps.argtypes = [_P, C.c_int, C.c_int, _P, _P, _P]
 lib.als_outer_apply_dn.argtypes = [_P, _P, C.c_int, C.c_int]
+lib.als_outer_apply_rule.argtypes = [_P, _P, C.c_int, C.c_int, C.POINTER(OuterRule)]
+lib.als_worker_staleness.restype = C.c_int64
+lib.als_worker_staleness.argtypes = [_P, C.c_int]
 lib.als_dylu_schedule.argtypes = [_P, C.c_int, C.c_int, C.c_double, C.c_int, _P, _P, _P, _P]
 lib.als_get_vector.argtypes = [_P, C.c_int, C.c_int, _P]
 lib.als_set_vector.argtypes = [_P, C.c_int, C.c_int, _P]
@@ -235,6 +244,16 @@ class Context:
     def outer_apply_dn(self, workers, restart: bool = True):
         w = np.ascontiguousarray(workers, dtype=np.int32)
         _check(lib.als_outer_apply_dn(self._ctx, _np_ptr(w), int(w.size), 1 if restart else 0))
+
+    def outer_apply_rule(self, workers, restart: bool = True, kind: int = RULE_DN, poly_exponent: float = 0.0,
+                         staleness_threshold: int = -1, dc_lambda: float = 0.0):
+        w = np.ascontiguousarray(workers, dtype=np.int32)
+        rule = OuterRule(kind=kind, staleness_threshold=staleness_threshold, poly_exponent=poly_exponent,
+                         dc_lambda=dc_lambda)
+        _check(lib.als_outer_apply_rule(self._ctx, _np_ptr(w), int(w.size), 1 if restart else 0, C.byref(rule)))
+
+    def staleness(self, worker: int) -> int:
+        return int(lib.als_worker_staleness(self._ctx, worker))
 
     def get_vector(self, which: str, worker: int = 0) -> np.ndarray:
         out = np.empty(self.P, dtype=np.float32)

@@ -114,6 +114,12 @@ struct DnGroup {
   int restart;
   unsigned boundary_mask;  // bit j set: event j is an N-th event
   float lr, beta, c_beta, cb_boundary, Nf;  // c*beta ; (1 - cN + c)*beta
+  // comparison rules of the paper's "Existing Fixes": per-event weight on the pseudo-gradient
+  // (polynomial staleness discount; 1 = none), delay-compensation strength lambda (0 = off),
+  // buffered mode (no parameter change between N-th events, which apply Nesterov on Delta/N)
+  float weight[ALS_DN_MAX_GROUP];
+  float dc_lambda;
+  int buffered;
 };
 int dn_group(float* theta, float* m, float* delta, const DnGroup& g, int64_t P, hipStream_t st);
 int restart_copy(const float* theta, float* master, float* start, bf16* lp, int64_t P,

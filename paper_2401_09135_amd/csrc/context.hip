@@ -24,6 +24,7 @@ struct Worker {
   int32_t *sort_offset, *sort_rank, *sort_pos;
   float* splitk_ws; size_t splitk_bytes;
   int64_t adam_n; int last_n;
+  int64_t t_restart;  // server event count when this replica last (re)started
   hipStream_t stream; hipEvent_t done_ev, ready_ev;
 };
 
@@ -251,7 +252,7 @@ extern "C" int als_init(const als_config* cfg, void* arena, size_t arena_bytes, 
   for (size_t i = 0; i < c->w.size(); i++) {
     Worker& w = c->w[i];
     w.stream = (hipStream_t)streams[i % n_streams];
-    w.adam_n = 0; w.last_n = 0;
+    w.adam_n = 0; w.last_n = 0; w.t_restart = 0;
     if (hipEventCreateWithFlags(&w.done_ev, hipEventDisableTiming) != hipSuccess ||
         hipEventCreateWithFlags(&w.ready_ev, hipEventDisableTiming) != hipSuccess ||
         hipHostMalloc((void**)&w.losses_host, (size_t)cfg->max_local_steps * 4, hipHostMallocDefault) != hipSuccess)
@@ -338,10 +339,13 @@ extern "C" int als_worker_loss_grad(als_ctx* ctx, int worker, const int32_t* tok
   return ALS_OK;
 }
 
-extern "C" int als_outer_apply_dn(als_ctx* ctx, const int32_t* workers, int n_group, int restart_flag) {
+static int outer_apply(als_ctx* ctx, const int32_t* workers, int n_group, int restart_flag, const als_outer_rule& rule) {
   if (!ctx || !workers) return set_error(ALS_ERR_INVALID, "null argument");
   int k = (int)ctx->w.size();
   if (n_group < 1 || n_group > k) return set_error(ALS_ERR_INVALID, "n_group %d outside 1..k", n_group);
+  if (rule.kind != ALS_RULE_DN && rule.kind != ALS_RULE_BUFFER) return set_error(ALS_ERR_INVALID, "unknown outer rule %d", rule.kind);
+  if (!(rule.poly_exponent >= 0) || !isfinite(rule.poly_exponent) || !isfinite(rule.dc_lambda) || rule.dc_lambda < 0)
+    return set_error(ALS_ERR_INVALID, "outer rule: poly_exponent and dc_lambda must be finite and >= 0");
   unsigned long long seen = 0;
   for (int j = 0; j < n_group; j++) {
     if (workers[j] < 0 || workers[j] >= k) return set_error(ALS_ERR_INVALID, "worker %d out of range", workers[j]);
@@ -353,22 +357,41 @@ extern "C" int als_outer_apply_dn(als_ctx* ctx, const int32_t* workers, int n_gr
   ALS_HIP(hipStreamWaitEvent(st, ctx->server_ev, 0));
   for (int j = 0; j < n_group; j++) ALS_HIP(hipStreamWaitEvent(st, ctx->w[workers[j]].done_ev, 0));
   int64_t P = ctx->L.P;
-  bool fused_restart = restart_flag && n_group <= ALS_DN_MAX_GROUP;
-  for (int j0 = 0; j0 < n_group; j0 += ALS_DN_MAX_GROUP) {
+  // Which events are applied: a worker whose staleness (server events since it started)
+  // exceeds the threshold is discarded -- no server change, no event counted -- but still restarts.
+  std::vector<int> applied;
+  std::vector<float> weight;
+  {
+    int64_t t = ctx->t;
+    for (int j = 0; j < n_group; j++) {
+      int64_t stale = t - ctx->w[workers[j]].t_restart;
+      if (rule.staleness_threshold >= 0 && stale > rule.staleness_threshold) continue;
+      applied.push_back(workers[j]);
+      weight.push_back(rule.poly_exponent > 0 ? (float)pow(1.0 + (double)stale, -rule.poly_exponent) : 1.0f);
+      t++;
+    }
+  }
+  int n_app = (int)applied.size();
+  bool fused_restart = restart_flag && n_app == n_group && n_group <= ALS_DN_MAX_GROUP;
+  for (int j0 = 0; j0 < n_app; j0 += ALS_DN_MAX_GROUP) {
     DnGroup dg;
     memset(&dg, 0, sizeof dg);
-    dg.G = n_group - j0 < ALS_DN_MAX_GROUP ? n_group - j0 : ALS_DN_MAX_GROUP;
+    dg.G = n_app - j0 < ALS_DN_MAX_GROUP ? n_app - j0 : ALS_DN_MAX_GROUP;
     dg.restart = fused_restart ? 1 : 0;
+    for (int j = 0; j < ALS_DN_MAX_GROUP; j++) dg.weight[j] = 1.0f;
     for (int j = 0; j < dg.G; j++) {
-      Worker& w = ctx->w[workers[j0 + j]];
+      Worker& w = ctx->w[applied[j0 + j]];
       dg.theta_start[j] = w.start; dg.theta_worker[j] = w.theta; dg.start_out[j] = w.start;
       dg.lp_out[j] = w.lp;
+      dg.weight[j] = weight[j0 + j];
       if ((ctx->t + j + 1) % g.dn_N == 0) dg.boundary_mask |= 1u << j;
     }
     dg.lr = (float)g.outer_lr; dg.beta = (float)g.outer_beta;
     dg.c_beta = (float)(g.dn_c * g.outer_beta);
     dg.cb_boundary = (float)((1.0 - g.dn_c * g.dn_N + g.dn_c) * g.outer_beta);
     dg.Nf = (float)g.dn_N;
+    dg.dc_lambda = (float)rule.dc_lambda;
+    dg.buffered = rule.kind == ALS_RULE_BUFFER;
     RUN(dn_group(ctx->theta, ctx->m, ctx->delta, dg, P, st));
     ctx->t += dg.G;
   }
@@ -377,6 +400,8 @@ extern "C" int als_outer_apply_dn(als_ctx* ctx, const int32_t* workers, int n_gr
       Worker& w = ctx->w[workers[j]];
       RUN(restart_copy(ctx->theta, w.theta, w.start, w.lp, P, st));
     }
+  if (restart_flag)
+    for (int j = 0; j < n_group; j++) ctx->w[workers[j]].t_restart = ctx->t;
   ALS_HIP(hipEventRecord(ctx->server_ev, st));
   // Whatever touches these replicas next (their local steps, or a later sync) is ordered
   // after this call.
@@ -385,6 +410,24 @@ extern "C" int als_outer_apply_dn(als_ctx* ctx, const int32_t* workers, int n_gr
     ALS_HIP(hipEventRecord(ctx->w[workers[j]].done_ev, st));
   }
   return ALS_OK;
+}
+
+extern "C" int als_outer_apply_dn(als_ctx* ctx, const int32_t* workers, int n_group, int restart_flag) {
+  als_outer_rule rule;
+  memset(&rule, 0, sizeof rule);
+  rule.kind = ALS_RULE_DN; rule.staleness_threshold = -1;
+  return outer_apply(ctx, workers, n_group, restart_flag, rule);
+}
+
+extern "C" int als_outer_apply_rule(als_ctx* ctx, const int32_t* workers, int n_group, int restart_flag,
+                                    const als_outer_rule* rule) {
+  if (!rule) return set_error(ALS_ERR_INVALID, "rule is null");
+  return outer_apply(ctx, workers, n_group, restart_flag, *rule);
+}
+
+extern "C" int64_t als_worker_staleness(als_ctx* ctx, int worker) {
+  if (check_ctx_worker(ctx, worker)) return -1;
+  return ctx->t - ctx->w[worker].t_restart;
 }
 
 extern "C" int als_sync(als_ctx* ctx, int worker) {
@@ -466,6 +509,7 @@ extern "C" int als_k_dn_group(float* theta, float* m, float* delta, float* const
   DnGroup dg;
   memset(&dg, 0, sizeof dg);
   dg.G = G; dg.restart = restart ? 1 : 0;
+  for (int j = 0; j < ALS_DN_MAX_GROUP; j++) dg.weight[j] = 1.0f;
   for (int j = 0; j < G; j++) {
     if (!theta_start[j] || !theta_worker[j]) return set_error(ALS_ERR_INVALID, "null worker vector");
     dg.theta_start[j] = theta_start[j]; dg.theta_worker[j] = theta_worker[j];

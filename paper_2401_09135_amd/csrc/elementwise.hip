@@ -139,9 +139,21 @@ int adamw(float* theta, const float* grad, float* m, float* v, bf16* lp, int64_t
 //   otherwise:   theta -= eps (c beta m + g/N)
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ void dn_event_scalar(float& th, float& mm, float& de, float ts, float tw,
-                                                bool boundary, bool use_m, const DnGroup& g) {
+                                                bool boundary, bool use_m, float wj, const DnGroup& g) {
   float gj = ts - tw;
+  // delay compensation: g + lambda g g (theta_now - theta_at_worker_start)
+  if (g.dc_lambda != 0.0f) gj = gj + g.dc_lambda * gj * gj * (th - ts);
+  if (wj != 1.0f) gj = wj * gj;  // staleness discount
   de += gj;
+  if (g.buffered) {  // buffered averaging: Nesterov on Delta/N at every N-th event, nothing in between
+    if (boundary) {
+      float gbar = de / g.Nf;
+      mm = g.beta * mm + gbar;
+      th = th - g.lr * (g.beta * mm + gbar);
+      de = 0.0f;
+    }
+    return;
+  }
   if (boundary) {
     mm = g.beta * mm + de / g.Nf;
     th = th - g.lr * (g.cb_boundary * mm + gj / g.Nf);
@@ -180,13 +192,14 @@ __global__ __launch_bounds__(256) void dn_group_kernel(float* theta, float* m, f
         if (i < n4) { ts[u] = ldnt(g.theta_start[j], i); tw[u] = ldnt(g.theta_worker[j], i); }
       }
       const bool boundary = (g.boundary_mask >> j) & 1u;
+      const float wj = g.weight[j];
 #pragma unroll
       for (int u = 0; u < U; u++)
         if (i0 + u * 256 < n4) {
 #pragma unroll
           for (int e = 0; e < 4; e++) {
             float t = th[u][e], mo = mm[u][e], d = de[u][e];
-            dn_event_scalar(t, mo, d, ts[u][e], tw[u][e], boundary, use_m, g);
+            dn_event_scalar(t, mo, d, ts[u][e], tw[u][e], boundary, use_m, wj, g);
             th[u][e] = t; mm[u][e] = mo; de[u][e] = d;
           }
         }
@@ -214,7 +227,7 @@ __global__ void dn_group_tail_kernel(float* theta, float* m, float* delta, DnGro
   const bool use_m = g.c_beta != 0.0f;
   float th = theta[i], de = delta[i], mm = (use_m || g.boundary_mask) ? m[i] : 0.0f;
   for (int j = 0; j < g.G; j++)
-    dn_event_scalar(th, mm, de, g.theta_start[j][i], g.theta_worker[j][i], (g.boundary_mask >> j) & 1u, use_m, g);
+    dn_event_scalar(th, mm, de, g.theta_start[j][i], g.theta_worker[j][i], (g.boundary_mask >> j) & 1u, use_m, g.weight[j], g);
   theta[i] = th; delta[i] = de;
   if (g.boundary_mask) m[i] = mm;
   if (g.restart)

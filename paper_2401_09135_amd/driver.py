@@ -9,7 +9,7 @@ from .binding import Config, Context, dylu_schedule
 
 
 def run_async(w: dict, theta0: np.ndarray, make_stream, n_events: int | None = None, flags: int = 0,
-              ctx: Context | None = None, collect_losses: bool = True, lr=None):
+              ctx: Context | None = None, collect_losses: bool = True, lr=None, rule: dict | None = None):
     """w: workload dict (als_inputs.workload); make_stream(i) -> object with take(n) giving
     int32 [n,B,S+1] token batches for worker i.  Returns dict like the oracle's run."""
     import torch
@@ -46,7 +46,10 @@ def run_async(w: dict, theta0: np.ndarray, make_stream, n_events: int | None = N
         complete = bool(ev_g[j])
         for i in group:
             harvest(i)
-        ctx.outer_apply_dn(group, restart=complete)
+        if rule:
+            ctx.outer_apply_rule(group, restart=complete, **rule)
+        else:
+            ctx.outer_apply_dn(group, restart=complete)
         if complete and j + 1 < n_events:
             for i in group:
                 train(i)

@@ -238,3 +238,52 @@ def test_event_trace_cut_mid_group_is_flagged():
     assert groups[-1]["complete"] is False and len(groups[-1]["events"]) == 1
     groups = event_trace([1.0, 1.0], [2, 2], 0.0, 4)
     assert groups[-1]["complete"] is True and len(groups) == 2
+
+
+# ------------------------------------------------- comparison rules ("Existing Fixes")
+def test_poly_weight_values():
+    from oracle.optim import poly_weight
+    assert poly_weight(0) == 1.0
+    assert poly_weight(3) == pytest.approx(0.5)
+    assert poly_weight(8) == pytest.approx(1.0 / 3.0)
+    assert poly_weight(3, 1.0) == pytest.approx(0.25)
+
+
+def test_delay_compensation_formula_and_identity():
+    from oracle.optim import delay_compensated
+    g = np.array([2.0, -1.0, 0.0])
+    now, then = np.array([1.0, 1.0, 5.0]), np.array([0.5, 2.0, 0.0])
+    np.testing.assert_array_equal(delay_compensated(g, now, then, 0.0), g)
+    # g + lam g^2 (now - then): 2 + .1*4*.5 = 2.2 ; -1 + .1*1*(-1) = -1.1 ; 0
+    np.testing.assert_allclose(delay_compensated(g, now, then, 0.1), [2.2, -1.1, 0.0], atol=1e-15)
+    np.testing.assert_array_equal(delay_compensated(g, then, then, 7.0), g)       # no drift, no correction
+
+
+def test_async_buffer_is_nesterov_on_the_mean_and_matches_dn_at_period_ends():
+    from oracle.optim import AsyncBuffer
+    rng = np.random.default_rng(4)
+    N = 4
+    th0 = rng.standard_normal(6)
+    buf = AsyncBuffer(th0, 0.7, 0.9, N)
+    dn = DelayedNesterov(th0, 0.7, 0.9, N, 0.0)
+    th, m = th0.copy(), np.zeros(6)
+    for _ in range(3):
+        gs = [rng.standard_normal(6) for _ in range(N)]
+        before = buf.theta.copy()
+        for j, g in enumerate(gs):
+            buf.event(g)
+            dn.event(g)
+            if j < N - 1:
+                np.testing.assert_array_equal(buf.theta, before)       # parameters wait for the buffer
+        th, m = nesterov_step(th, m, sum(gs) / N, 0.7, 0.9)
+        np.testing.assert_allclose(buf.theta, th, atol=1e-12)
+        np.testing.assert_allclose(buf.m, m, atol=1e-12)
+        # with the same pseudo-gradients Delayed Nesterov (c = 0) lands on the same point every N events
+        np.testing.assert_allclose(dn.theta, buf.theta, atol=1e-12)
+    b1 = AsyncBuffer(th0, 0.7, 0.9, 1)                                   # N = 1 is plain Nesterov
+    th, m = th0.copy(), np.zeros(6)
+    for _ in range(4):
+        g = rng.standard_normal(6)
+        b1.event(g)
+        th, m = nesterov_step(th, m, g, 0.7, 0.9)
+        np.testing.assert_allclose(b1.theta, th, atol=1e-13)

@@ -63,3 +63,19 @@ def test_tiny_run_lowers_loss_and_follows_trace():
     assert r["t"] == 12 and r["theta"].dtype == np.float32
     assert r["steps"].tolist() == [1, 2, 3, 5]
     assert np.mean(r["losses"][3][-3:]) < np.mean(r["losses"][3][:3]) - 0.1
+
+
+def test_staleness_counts_and_threshold_drop():
+    # speeds (1, 1.5, 2, 3), H = 5: hand-traced order 0 1 2 3 0 1 (0 2) 3 (0 1) 2; staleness of
+    # an update = server events since its worker restarted: first four 0 1 2 3, then w0 (restarted
+    # after event 1, synced as event 5) 3, w1 3, w0 1, w2 4 ...
+    cfg = dict(I.workload("tiny"), N=1)
+    th0 = I.theta0(lm.param_layout(cfg), 0)
+    r = run.run_async(cfg, th0, _stream(cfg), n_events=8, rule=dict(poly_exponent=0.5))
+    assert r["staleness"] == [0, 1, 2, 3, 3, 3, 1, 4]
+    # with a threshold of 2 every update staler than 2 is dropped and does not count as an event,
+    # so later updates look less stale: 0 1 2 [3 dropped] then w0: 3 - 1 = 2, w1: 4 - 2 = 2,
+    # w0: 5 - 4 = 1, w2: 6 - 3 = 3 [dropped]
+    r2 = run.run_async(cfg, th0, _stream(cfg), n_events=8, rule=dict(poly_exponent=0.5, staleness_threshold=2))
+    assert r2["staleness"] == [0, 1, 2, 3, 2, 2, 1, 3]
+    assert r2["t"] == 6
