@@ -39,6 +39,21 @@ WORKLOADS = {
     # seconds, still several GEMM/attention tiles with ragged step counts).
     "mini_bf16": dict(_COMMON, L=2, d=256, h=4, ff=1024, V=1024, S=128, B=4, dtype="bf16",
                       k=4, speeds=[1.0, 1.2, 1.6, 2.4], H=10, N=4, n_events=4),
+    # The paper's own model table (appendix, Model Configuration): 20M = 6 layers, hidden 256, 4
+    # heads; 60M = 3 layers, hidden 896, 16 heads; 150M = 12 layers, hidden 896, 16 heads; K/V
+    # size 64 (so the attention width of the two larger models is 1024, not 896), vocabulary
+    # 32000, sequence 256.  FFN width 4 d (not printed).  Small per-worker batches for tests.
+    "paper20m": dict(_COMMON, L=6, d=256, h=4, dh=64, ff=1024, V=32000, S=256, B=2, dtype="bf16",
+                     k=2, speeds=[1.0, 2.0], H=2, N=2, n_events=2),
+    "paper60m": dict(_COMMON, L=3, d=896, h=16, dh=64, ff=3584, V=32000, S=256, B=2, dtype="bf16",
+                     k=2, speeds=[1.0, 2.0], H=2, N=2, n_events=2),
+    "paper150m": dict(_COMMON, L=12, d=896, h=16, dh=64, ff=3584, V=32000, S=256, B=2, dtype="bf16",
+                      k=2, speeds=[1.0, 2.0], H=2, N=2, n_events=2),
+    # the paper's 150M model at its own per-worker batch (128 sequences of 256): a bench workload
+    "paper150m_b128": dict(_COMMON, L=12, d=896, h=16, dh=64, ff=3584, V=32000, S=256, B=128,
+                           dtype="bf16", k=4, speeds=[1.0, 1.2, 1.6, 2.4], H=50, N=4, n_events=4),
+    "wide_attn_f32": dict(_COMMON, L=2, d=64, h=4, dh=32, ff=128, V=200, S=24, B=3, dtype="f32",
+                          k=2, speeds=[1.0, 2.0], H=2, N=2, n_events=4),
     # the 150M-class architecture on one 1024-token sequence per step (d 896 = 7 x 128, 14 heads,
     # V 32000, S 1024): every kernel shape class of BASELINE configs[3] at 1/16 of its batch
     "lm150m_b1": dict(_COMMON, L=12, d=896, h=14, ff=3584, V=32000, S=1024, B=1, dtype="bf16",

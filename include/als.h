@@ -21,8 +21,9 @@
  *     callers' own buffers: als_init() carves everything out of one caller-owned arena.
  *     Streams are borrowed hipStream_t handles passed as void*.
  *   - Flat parameter vector layout (row-major tensors, fp32), P elements in total:
- *       E [V,d], Ppos [S,d], per layer: Wqkv [d,3d] (columns q|k|v, head-major inside each),
- *       Wo [d,d], W1 [d,ff], W2 [ff,d]; Wout [d,V]; then the RMSNorm gains: per layer g1 [d],
+ *       E [V,d], Ppos [S,d], per layer: Wqkv [d,3a] (columns q|k|v, head-major inside each,
+ *       a = h * head width = attention width, equal to d unless head_dim is set), Wo [a,d],
+ *       W1 [d,ff], W2 [ff,d]; Wout [d,V]; then the RMSNorm gains: per layer g1 [d],
  *       g2 [d]; finally gf [d].  The first P_decay elements (everything but the gains) are
  *       weight-decayed.
  *   - Model (reading of "decoder-only transformer", appendix "Network Architecture"):
@@ -55,7 +56,7 @@ extern "C" {
 typedef struct als_config {
   int32_t n_layers;        /* L */
   int32_t d_model;         /* d, multiple of 64 */
-  int32_t n_heads;         /* h, d/h in {32, 64} */
+  int32_t n_heads;         /* h; head width = head_dim if set, else d/h; must be 32 or 64 */
   int32_t d_ff;            /* ff, multiple of 64 */
   int32_t vocab;           /* V */
   int32_t seq_len;         /* S (tokens carry S+1 per sample), <= 1024 */
@@ -65,6 +66,9 @@ typedef struct als_config {
   int32_t dn_N;            /* N >= 1 */
   int32_t max_local_steps; /* capacity of the per-worker loss buffer (>= largest n_steps) */
   int32_t flags;           /* bit 0: disable the MFMA kernels (use the generic ones) */
+  int32_t head_dim;        /* 0 = d/h; otherwise the attention width h*head_dim may differ from d
+                              (the paper's 60M / 150M models: 16 heads of 64 on d = 896) */
+  int32_t reserved0;       /* keeps the doubles 8-byte aligned; must be 0 */
   double adam_beta1, adam_beta2, adam_eps, weight_decay; /* AdamW (inner optimiser) */
   double outer_lr, outer_beta, dn_c;                     /* Alg. 3: epsilon, beta, c in [0,1/N] */
   double norm_eps;                                       /* RMSNorm epsilon */

@@ -8,8 +8,9 @@ absolute position embeddings, no biases, no dropout, untied input/output embeddi
 averaged over all B*S predicted positions.
 
 Flat parameter vector layout (all row-major):
-  E [V,d], Ppos [S,d], then per layer Wqkv [d,3d] (columns q|k|v, head-major inside each),
-  Wo [d,d], W1 [d,ff], W2 [ff,d]; then Wout [d,V]; then all gains: per layer g1 [d], g2 [d];
+  E [V,d], Ppos [S,d], then per layer Wqkv [d,3a] (columns q|k|v, head-major inside each;
+  a = attention width = h * head width, equal to d unless cfg["dh"] is set), Wo [a,d],
+  W1 [d,ff], W2 [ff,d]; then Wout [d,V]; then all gains: per layer g1 [d], g2 [d];
   finally gf [d].  Everything before the gains is weight-decayed, the gains are not.
 """
 from __future__ import annotations
@@ -18,12 +19,19 @@ import math
 import numpy as np
 
 
+def attention_width(cfg):
+    """h * head width; the head width is cfg["dh"] if given (the paper's 60M and 150M models
+    use 16 heads of 64 on a hidden size of 896), else d / h."""
+    return cfg["h"] * (cfg.get("dh") or cfg["d"] // cfg["h"])
+
+
 def param_layout(cfg):
     """List of (name, shape, kind); kind is "matrix" (decayed) or "gain" (not decayed)."""
     L, d, ff, V, S = cfg["L"], cfg["d"], cfg["ff"], cfg["V"], cfg["S"]
+    da = attention_width(cfg)
     out = [("E", (V, d), "matrix"), ("Ppos", (S, d), "matrix")]
     for l in range(L):
-        out += [(f"Wqkv{l}", (d, 3 * d), "matrix"), (f"Wo{l}", (d, d), "matrix"),
+        out += [(f"Wqkv{l}", (d, 3 * da), "matrix"), (f"Wo{l}", (da, d), "matrix"),
                 (f"W1{l}", (d, ff), "matrix"), (f"W2{l}", (ff, d), "matrix")]
     out.append(("Wout", (d, V), "matrix"))
     for l in range(L):
@@ -122,6 +130,7 @@ def forward(theta, tokens, cfg, keep=True):
     """tokens int [B,S+1].  Returns (loss, cache).  Also cache["logits"] [B*S,V]."""
     p = views(theta, cfg)
     L, d, h, S = cfg["L"], cfg["d"], cfg["h"], cfg["S"]
+    da = attention_width(cfg)
     eps = cfg["norm_eps"]
     B = tokens.shape[0]
     assert tokens.shape[1] == S + 1
@@ -131,9 +140,9 @@ def forward(theta, tokens, cfg, keep=True):
     for l in range(L):
         a, rstd1 = rmsnorm_fwd(x, p[f"g1{l}"], eps)
         qkv = a @ p[f"Wqkv{l}"]
-        q = _split_heads(qkv[:, :d], B, S, h)
-        k = _split_heads(qkv[:, d:2 * d], B, S, h)
-        v = _split_heads(qkv[:, 2 * d:], B, S, h)
+        q = _split_heads(qkv[:, :da], B, S, h)
+        k = _split_heads(qkv[:, da:2 * da], B, S, h)
+        v = _split_heads(qkv[:, 2 * da:], B, S, h)
         o4, prob = attention_fwd(q, k, v)
         o = _merge_heads(o4)
         xm = x + o @ p[f"Wo{l}"]

@@ -34,6 +34,7 @@ struct Layout {
   int64_t P, P_decay;
 };
 int validate_config(const als_config* c);
+int head_width(const als_config& c);  // head_dim, or d/h when head_dim is 0
 void make_layout(const als_config& c, Layout* L);
 
 // ---- GEMM -------------------------------------------------------------------------------

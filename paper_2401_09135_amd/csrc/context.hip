@@ -60,6 +60,7 @@ void carve(als_ctx* c, Carver& cv) {
   const als_config& g = c->cfg;
   bool bf = g.dtype == ALS_DTYPE_BF16;
   int64_t P = c->L.P, T = (int64_t)g.batch * g.seq_len, d = g.d_model, ff = g.d_ff, V = g.vocab;
+  int64_t da = (int64_t)g.n_heads * head_width(g);  // attention width
   int64_t BhS = (int64_t)g.batch * g.n_heads * g.seq_len;
   c->theta = cv.f32(P); c->m = cv.f32(P); c->delta = cv.f32(P);
   c->w.resize(g.n_workers);
@@ -73,15 +74,15 @@ void carve(als_ctx* c, Carver& cv) {
     for (int l = 0; l <= L; l++) w.x[l] = cv.f32(T * d);
     for (int l = 0; l < L; l++) {
       w.xm[l] = cv.f32(T * d); w.rstd1[l] = cv.f32(T); w.rstd2[l] = cv.f32(T); w.lse[l] = cv.f32(BhS);
-      w.a[l] = cv.act(T * d, bf); w.qkv[l] = cv.act(T * 3 * d, bf); w.o[l] = cv.act(T * d, bf);
+      w.a[l] = cv.act(T * d, bf); w.qkv[l] = cv.act(T * 3 * da, bf); w.o[l] = cv.act(T * da, bf);
       w.b[l] = cv.act(T * d, bf); w.u[l] = cv.act(T * ff, bf); w.gl[l] = cv.act(T * ff, bf);
     }
     w.xf = cv.act(T * d, bf); w.rstdf = cv.f32(T);
     w.logits = cv.f32(T * V); w.dlogits = cv.act(T * V, bf); w.loss_row = cv.f32(T);
     w.dxa = cv.f32(T * d); w.dxb = cv.f32(T * d); w.dtmp = cv.f32(T * d); w.Dbuf = cv.f32(BhS);
     w.partial = cv.f32((int64_t)rmsnorm_bwd_blocks((int)T) * d);
-    w.dx_lp = cv.act(T * d, bf); w.dff = cv.act(T * ff, bf); w.d_o = cv.act(T * d, bf);
-    w.dqkv = cv.act(T * 3 * d, bf);
+    w.dx_lp = cv.act(T * d, bf); w.dff = cv.act(T * ff, bf); w.d_o = cv.act(T * da, bf);
+    w.dqkv = cv.act(T * 3 * da, bf);
     w.losses_dev = cv.f32(g.max_local_steps);
     w.sort_offset = (int32_t*)cv.take((size_t)g.max_local_steps * (V + 1) * 4);
     w.sort_rank = (int32_t*)cv.take((size_t)g.max_local_steps * T * 4);
@@ -89,7 +90,7 @@ void carve(als_ctx* c, Carver& cv) {
     // split-K partials of the weight-gradient GEMMs: up to 16 copies of the largest layer
     // matrix, capped at 64 MiB
     {
-      int64_t big = d * (ff > 3 * d ? ff : 3 * d);
+      int64_t big = d * (ff > 3 * da ? ff : 3 * da);
       size_t want = (size_t)big * 4 * 16;
       w.splitk_bytes = bf ? (want < ((size_t)64 << 20) ? want : ((size_t)64 << 20)) : 0;
       w.splitk_ws = w.splitk_bytes ? (float*)cv.take(w.splitk_bytes) : nullptr;
@@ -127,17 +128,18 @@ int forward(als_ctx* c, Worker& w, const int32_t* tok, float* loss_out) {
   const Layout& L = c->L;
   hipStream_t st = w.stream;
   int T = c->T, d = g.d_model, ff = g.d_ff, V = g.vocab, B = g.batch, S = g.seq_len, h = g.n_heads;
+  const int dh = head_width(g), da = h * dh;
   bool mf = c->allow_mfma;
   float eps = (float)g.norm_eps;
   RUN(embed_fwd(tok, w.theta + L.E, w.theta + L.Ppos, w.x[0], B, S, d, V, st));
   for (int l = 0; l < g.n_layers; l++) {
     RUN(rmsnorm_fwd(w.x[l], w.theta + L.g1[l], w.a[l], w.rstd1[l], T, d, eps, c->bf, st));
-    RUN(gemm(desc(c, w.a[l], 0, d, wptr(c, w, L.Wqkv[l]), 0, 3 * d, T, 3 * d, d, w.qkv[l], 3 * d, true), mf, st));
-    if (mf && attention_mfma_supported(S, d / h, c->bf))
-      RUN(attention_fwd_mfma(w.qkv[l], w.o[l], w.lse[l], B, S, h, d / h, st));
+    RUN(gemm(desc(c, w.a[l], 0, d, wptr(c, w, L.Wqkv[l]), 0, 3 * da, T, 3 * da, d, w.qkv[l], 3 * da, true), mf, st));
+    if (mf && attention_mfma_supported(S, dh, c->bf))
+      RUN(attention_fwd_mfma(w.qkv[l], w.o[l], w.lse[l], B, S, h, dh, st));
     else
-      RUN(attention_fwd_generic(w.qkv[l], w.o[l], w.lse[l], B, S, h, d / h, c->bf, st));
-    GemmDesc po = desc(c, w.o[l], 0, d, wptr(c, w, L.Wo[l]), 0, d, T, d, d, w.xm[l], d, false);
+      RUN(attention_fwd_generic(w.qkv[l], w.o[l], w.lse[l], B, S, h, dh, c->bf, st));
+    GemmDesc po = desc(c, w.o[l], 0, da, wptr(c, w, L.Wo[l]), 0, d, T, d, da, w.xm[l], d, false);
     po.epi = EPI_RESID; po.R = w.x[l]; po.ldr = d;
     RUN(gemm(po, mf, st));
     RUN(rmsnorm_fwd(w.xm[l], w.theta + L.g2[l], w.b[l], w.rstd2[l], T, d, eps, c->bf, st));
@@ -160,6 +162,7 @@ int backward(als_ctx* c, Worker& w, int slot) {
   const Layout& L = c->L;
   hipStream_t st = w.stream;
   int T = c->T, d = g.d_model, ff = g.d_ff, V = g.vocab, B = g.batch, S = g.seq_len, h = g.n_heads;
+  const int dh = head_width(g), da = h * dh;
   bool mf = c->allow_mfma;
   int nl = g.n_layers;
   // output matrix and final norm
@@ -178,14 +181,14 @@ int backward(als_ctx* c, Worker& w, int slot) {
     RUN(rmsnorm_bwd(w.dtmp, w.xm[l], w.rstd2[l], w.theta + L.g2[l], w.dxa, w.dxb, w.dx_lp, c->bf,
                     w.grad + L.g2[l], w.partial, T, d, st));
     // attention block: xm = x + attn(a Wqkv) Wo
-    RUN(gemm(desc_dw(c, w, w.o[l], d, w.dx_lp, d, d, d, T, w.grad + L.Wo[l]), mf, st));
-    RUN(gemm(desc(c, w.dx_lp, 0, d, wptr(c, w, L.Wo[l]), 1, d, T, d, d, w.d_o, d, true), mf, st));
-    if (mf && attention_mfma_supported(S, d / h, c->bf))
-      RUN(attention_bwd_mfma(w.qkv[l], w.o[l], w.d_o, w.lse[l], w.Dbuf, w.dqkv, B, S, h, d / h, st));
+    RUN(gemm(desc_dw(c, w, w.o[l], da, w.dx_lp, d, da, d, T, w.grad + L.Wo[l]), mf, st));
+    RUN(gemm(desc(c, w.dx_lp, 0, d, wptr(c, w, L.Wo[l]), 1, d, T, da, d, w.d_o, da, true), mf, st));
+    if (mf && attention_mfma_supported(S, dh, c->bf))
+      RUN(attention_bwd_mfma(w.qkv[l], w.o[l], w.d_o, w.lse[l], w.Dbuf, w.dqkv, B, S, h, dh, st));
     else
-      RUN(attention_bwd_generic(w.qkv[l], w.o[l], w.d_o, w.lse[l], w.Dbuf, w.dqkv, B, S, h, d / h, c->bf, st));
-    RUN(gemm(desc_dw(c, w, w.a[l], d, w.dqkv, 3 * d, d, 3 * d, T, w.grad + L.Wqkv[l]), mf, st));
-    RUN(gemm(desc(c, w.dqkv, 0, 3 * d, wptr(c, w, L.Wqkv[l]), 1, 3 * d, T, d, 3 * d, w.dtmp, d, false), mf, st));
+      RUN(attention_bwd_generic(w.qkv[l], w.o[l], w.d_o, w.lse[l], w.Dbuf, w.dqkv, B, S, h, dh, c->bf, st));
+    RUN(gemm(desc_dw(c, w, w.a[l], d, w.dqkv, 3 * da, d, 3 * da, T, w.grad + L.Wqkv[l]), mf, st));
+    RUN(gemm(desc(c, w.dqkv, 0, 3 * da, wptr(c, w, L.Wqkv[l]), 1, 3 * da, T, d, 3 * da, w.dtmp, d, false), mf, st));
     RUN(rmsnorm_bwd(w.dtmp, w.x[l], w.rstd1[l], w.theta + L.g1[l], w.dxb, w.dxa, w.dx_lp, c->bf,
                     w.grad + L.g1[l], w.partial, T, d, st));
   }

@@ -20,14 +20,19 @@ int set_error(int code, const char* fmt, ...) {
   return code;
 }
 
+int head_width(const als_config& c);
+
 int validate_config(const als_config* c) {
   if (!c) return set_error(ALS_ERR_INVALID, "config is null");
   if (c->n_layers < 1 || c->n_layers > 64) return set_error(ALS_ERR_INVALID, "n_layers must be in 1..64");
   if (c->d_model < 64 || c->d_model % 64 || c->d_model > 1024)
     return set_error(ALS_ERR_INVALID, "d_model must be a multiple of 64 in 64..1024");
-  if (c->n_heads < 1 || c->d_model % c->n_heads) return set_error(ALS_ERR_INVALID, "d_model must be divisible by n_heads");
-  int dh = c->d_model / c->n_heads;
-  if (dh != 32 && dh != 64) return set_error(ALS_ERR_INVALID, "head width d_model/n_heads must be 32 or 64");
+  if (c->n_heads < 1) return set_error(ALS_ERR_INVALID, "n_heads must be >= 1");
+  if (c->head_dim < 0 || c->reserved0 != 0) return set_error(ALS_ERR_INVALID, "head_dim must be >= 0 and reserved0 zero");
+  if (c->head_dim == 0 && c->d_model % c->n_heads) return set_error(ALS_ERR_INVALID, "d_model must be divisible by n_heads");
+  int dh = head_width(*c);
+  if (dh != 32 && dh != 64) return set_error(ALS_ERR_INVALID, "head width must be 32 or 64");
+  if ((c->n_heads * dh) % 64 || c->n_heads * dh > 2048) return set_error(ALS_ERR_INVALID, "attention width h*head width must be a multiple of 64, at most 2048");
   if (c->d_ff < 64 || c->d_ff % 64) return set_error(ALS_ERR_INVALID, "d_ff must be a positive multiple of 64");
   if (c->vocab < 2) return set_error(ALS_ERR_INVALID, "vocab must be >= 2");
   if (c->seq_len < 1 || c->seq_len > 1024) return set_error(ALS_ERR_INVALID, "seq_len must be in 1..1024");
@@ -49,13 +54,16 @@ int validate_config(const als_config* c) {
   return ALS_OK;
 }
 
+int head_width(const als_config& c) { return c.head_dim ? c.head_dim : c.d_model / c.n_heads; }
+
 void make_layout(const als_config& c, Layout* L) {
   int64_t d = c.d_model, ff = c.d_ff, V = c.vocab, S = c.seq_len, off = 0;
+  int64_t da = (int64_t)c.n_heads * head_width(c);  // attention width
   L->E = off; off += V * d;
   L->Ppos = off; off += S * d;
   for (int l = 0; l < c.n_layers; l++) {
-    L->Wqkv[l] = off; off += d * 3 * d;
-    L->Wo[l] = off; off += d * d;
+    L->Wqkv[l] = off; off += d * 3 * da;
+    L->Wo[l] = off; off += da * d;
     L->W1[l] = off; off += d * ff;
     L->W2[l] = off; off += ff * d;
   }

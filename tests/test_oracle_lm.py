@@ -10,6 +10,10 @@ import als_inputs as I
 from oracle import lm
 
 CFG = dict(L=2, d=16, h=2, ff=40, V=23, S=6, norm_eps=1e-5)
+# attention width h * dh = 24 on a hidden size of 16 (the paper's larger models have 16 heads of
+# 64 on 896)
+CFG_WIDE = dict(L=2, d=16, h=3, dh=8, ff=40, V=23, S=6, norm_eps=1e-5)
+BOTH = pytest.mark.parametrize("CFG", [CFG, CFG_WIDE], ids=["square", "wide"])
 
 
 def _theta(cfg, seed=0, sigma=0.3, dtype=np.float64):
@@ -33,7 +37,18 @@ def test_layout_counts():
     assert lm.n_params(I.workload("lm20m")) == 27_531_776
 
 
-def test_gradient_matches_central_finite_differences_every_tensor():
+def test_layout_counts_wide_attention():
+    c = CFG_WIDE
+    shapes = {n: sh for n, sh, _ in lm.param_layout(c)}
+    assert shapes["Wqkv0"] == (16, 72) and shapes["Wo1"] == (24, 16)
+    assert lm.n_params(c) == lm.n_params(CFG) + c["L"] * (16 * 3 * 8 + 8 * 16)
+    # the paper's 150M row: 12 layers, 896 hidden, 16 heads of 64
+    p = dict(L=12, d=896, h=16, dh=64, ff=3584, V=32000, S=256)
+    assert lm.n_params(p) == 2 * 32000 * 896 + 256 * 896 + 12 * (896 * 3072 + 1024 * 896 + 2 * 896 * 3584) + 25 * 896
+
+
+@BOTH
+def test_gradient_matches_central_finite_differences_every_tensor(CFG):
     th = _theta(CFG)
     tok = _tokens(CFG)
     _, grad = lm.loss_and_grad(th, tok, CFG)
@@ -54,7 +69,8 @@ def test_gradient_matches_central_finite_differences_every_tensor():
     assert unused and not g["E"][unused].any()
 
 
-def test_directional_derivative_full_vector():
+@BOTH
+def test_directional_derivative_full_vector(CFG):
     th = _theta(CFG, seed=4)
     tok = _tokens(CFG, seed=4)
     _, grad = lm.loss_and_grad(th, tok, CFG)
@@ -67,6 +83,7 @@ def test_directional_derivative_full_vector():
 def _torch_loss(theta_t, tok, cfg):
     """The same model written independently with library ops and autograd."""
     L, d, h, ff, V, S = (cfg[k] for k in ("L", "d", "h", "ff", "V", "S"))
+    dh = cfg.get("dh", d // h)
     off = 0
 
     def take(*shape):
@@ -77,7 +94,7 @@ def _torch_loss(theta_t, tok, cfg):
         return t
 
     E, Ppos = take(V, d), take(S, d)
-    mats = [(take(d, 3 * d), take(d, d), take(d, ff), take(ff, d)) for _ in range(L)]
+    mats = [(take(d, 3 * h * dh), take(h * dh, d), take(d, ff), take(ff, d)) for _ in range(L)]
     Wout = take(d, V)
     gains = [(take(d), take(d)) for _ in range(L)]
     gf = take(d)
@@ -86,17 +103,18 @@ def _torch_loss(theta_t, tok, cfg):
     x = F.embedding(tok[:, :S], E) + Ppos
     for (Wqkv, Wo, W1, W2), (g1, g2) in zip(mats, gains):
         a = F.rms_norm(x, (d,), g1, cfg["norm_eps"])
-        q, k, v = (a @ Wqkv).split(d, dim=-1)
-        q, k, v = (z.view(B, S, h, d // h).transpose(1, 2) for z in (q, k, v))
+        q, k, v = (a @ Wqkv).split(h * dh, dim=-1)
+        q, k, v = (z.view(B, S, h, dh).transpose(1, 2) for z in (q, k, v))
         o = F.scaled_dot_product_attention(q, k, v, is_causal=True)
-        x = x + o.transpose(1, 2).reshape(B, S, d) @ Wo
+        x = x + o.transpose(1, 2).reshape(B, S, h * dh) @ Wo
         b = F.rms_norm(x, (d,), g2, cfg["norm_eps"])
         x = x + F.gelu(b @ W1, approximate="tanh") @ W2
     logits = F.rms_norm(x, (d,), gf, cfg["norm_eps"]) @ Wout
     return F.cross_entropy(logits.view(B * S, V), tok[:, 1:].reshape(-1))
 
 
-def test_loss_and_gradient_match_library_autograd():
+@BOTH
+def test_loss_and_gradient_match_library_autograd(CFG):
     th = _theta(CFG, seed=2)
     tok = _tokens(CFG, B=4, seed=2)
     loss, grad = lm.loss_and_grad(th, tok, CFG)
