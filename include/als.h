@@ -222,8 +222,9 @@ int als_k_gemm(const void* A, const void* B, void* C, int M, int N, int K, int a
 int als_k_gemm_ex(const void* A, const void* B, void* C, int M, int N, int K, int a_layout,
                   int b_layout, int in_dtype, int out_dtype, int use_mfma, int epi, const float* R,
                   void* C2, const void* U, void* ws_dev, size_t ws_bytes, void* stream);
-/* Benchmark hooks.  als_prof_enable(1) makes every MFMA GEMM launch record a HIP event before
- * and after itself on its own stream; als_prof_collect waits for the device and returns, per
+/* Benchmark hooks.  als_prof_enable(n), n >= 1, makes every n-th MFMA GEMM launch record a HIP
+ * event before and after itself on its own stream (a timed launch costs about 20 us of host
+ * time and orders the stream around it, so a throughput run samples); 0 switches it off; als_prof_collect waits for the device and returns, per
  * kernel instantiation (id), the number of launches, their summed duration in ms and their
  * summed algorithmic FLOPs (2 M N K), then forgets them.  Returns the number of entries
  * written (<= max_entries) or a negative error.  als_prof_kernel_name writes the kernel's

@@ -104,8 +104,9 @@ lib.als_prof_kernel_name.argtypes = [C.c_int, C.c_char_p, C.c_int]
 lib.als_k_set_gemm_tile.argtypes = [C.c_int, C.c_int, C.c_int]
 
 
-def prof_enable(on: bool) -> None:
-    _check(lib.als_prof_enable(1 if on else 0))
+def prof_enable(on) -> None:
+    """True / 1: time every MFMA GEMM launch; n > 1: every n-th; False / 0: off."""
+    _check(lib.als_prof_enable(int(on)))
 
 
 def prof_collect(max_entries: int = 64):

@@ -437,16 +437,30 @@ __global__ __launch_bounds__(64 * NW) void embed_bwd_rows_kernel(const int32_t* 
   float4 acc[EMB_MAXD4];
 #pragma unroll
   for (int s = 0; s < EMB_MAXD4; s++) acc[s] = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int r = beg + w; r < end; r += NW) {
-    const float4* row = reinterpret_cast<const float4*>(dx + (int64_t)pos[r] * d);
+  // A wave takes every NW-th position of the row's list, UNR of them in flight at a time (the
+  // few very frequent tokens have thousands of positions: the loop is bound by load latency);
+  // they are added in list order whatever UNR is.
+  constexpr int UNR = 8;
+  for (int r0 = beg + w; r0 < end; r0 += NW * UNR) {
+    float4 x[UNR][EMB_MAXD4];
 #pragma unroll
-    for (int s = 0; s < EMB_MAXD4; s++) {
-      int c = lane + 64 * s;
-      if (c < d4) {
-        float4 x = row[c];
-        acc[s].x += x.x; acc[s].y += x.y; acc[s].z += x.z; acc[s].w += x.w;
+    for (int u = 0; u < UNR; u++) {
+      int r = r0 + u * NW;
+      const float4* row = reinterpret_cast<const float4*>(dx + (int64_t)pos[r < end ? r : beg] * d);
+#pragma unroll
+      for (int s = 0; s < EMB_MAXD4; s++) {
+        int c = lane + 64 * s;
+        x[u][s] = (r < end && c < d4) ? row[c] : make_float4(0.f, 0.f, 0.f, 0.f);
       }
     }
+#pragma unroll
+    for (int u = 0; u < UNR; u++)
+      if (r0 + u * NW < end) {
+#pragma unroll
+        for (int s = 0; s < EMB_MAXD4; s++) {
+          acc[s].x += x[u][s].x; acc[s].y += x[u][s].y; acc[s].z += x[u][s].z; acc[s].w += x[u][s].w;
+        }
+      }
   }
 #pragma unroll
   for (int s = 0; s < EMB_MAXD4; s++) {

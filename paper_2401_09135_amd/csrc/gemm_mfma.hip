@@ -6,7 +6,7 @@
 // MFMA blocks.  Operands may be stored with the contraction index contiguous (read from LDS
 // with 16-byte loads, rows padded by 16 bytes so that 8 neighbouring rows hit different banks)
 // or with the contraction index strided (read with the LDS transpose load ds_read_b64_tr_b16,
-// rows padded by 32 bytes), so forward (x W), input-gradient (dY W^T) and weight-gradient
+// rows padded by 64 bytes), so forward (x W), input-gradient (dY W^T) and weight-gradient
 // (X^T dY) products all read the tensors as they lie in memory, without transposed copies.
 // Weight-gradient products have small M x N and very long K: they are split along K over
 // grid.z into fp32 partials that a second kernel adds in a fixed order.
@@ -35,6 +35,8 @@ constexpr int BK = 64;
 struct ProfRec { hipEvent_t e0, e1; int id; double flops; };
 std::mutex g_prof_mu;
 bool g_prof_on = false;
+int g_prof_every = 1;        // time one launch in g_prof_every
+unsigned g_prof_count = 0;
 std::vector<ProfRec> g_prof;
 
 int kernel_id(int bm, int bn, int al, int bl, int epi, int to_bf16, int split, int nbuf) {
@@ -44,13 +46,13 @@ int kernel_id(int bm, int bn, int al, int bl, int epi, int to_bf16, int split, i
 template <int BM, int BN, int AL, int BL, int NBUF>
 struct Tile {
   // AL == 0: A tile kept as [BM rows][64 k] ; AL == 1: as [64 k][BM rows]
-  static constexpr int A_STRIDE = AL == 0 ? BK * 2 + 16 : BM * 2 + 32;
+  static constexpr int A_STRIDE = AL == 0 ? BK * 2 + 16 : BM * 2 + 64;
   static constexpr int A_BYTES = A_STRIDE * (AL == 0 ? BM : BK);
   // BL == 1: B tile kept as [BN cols][64 k] ; BL == 0: as [64 k][BN cols]
-  static constexpr int B_STRIDE = BL == 1 ? BK * 2 + 16 : BN * 2 + 32;
+  static constexpr int B_STRIDE = BL == 1 ? BK * 2 + 16 : BN * 2 + 64;
   static constexpr int B_BYTES = B_STRIDE * (BL == 1 ? BN : BK);
   static constexpr int STAGE = A_BYTES + B_BYTES;
-  static constexpr int LDS_BYTES = NBUF * STAGE;
+  static constexpr int LDS_BYTES = (NBUF == 2 ? 2 : 1) * STAGE;
   static constexpr int A_CHUNKS = BM * BK * 2 / 16 / 256;  // 16-byte chunks per thread
   static constexpr int B_CHUNKS = BN * BK * 2 / 16 / 256;
 };
@@ -124,46 +126,48 @@ __global__ __launch_bounds__(256, OCC) void gemm_mfma_kernel(MfmaArgs g) {
   const int m0 = (tile / g.tiles_n) * BM, n0 = (tile % g.tiles_n) * BN;
   const int64_t kbase = (int64_t)zsplit * g.K;
 
-  const bf16* Ag = AL == 0 ? g.A + (int64_t)m0 * g.lda + kbase : g.A + kbase * g.lda + m0;
-  const bf16* Bg = BL == 1 ? g.B + (int64_t)n0 * g.ldb + kbase : g.B + kbase * g.ldb + n0;
+  // Global addressing: one 32-bit per-lane byte offset per operand; everything else (tile
+  // origin, 16-byte chunk index, K slice) is uniform and lives in scalar registers, so a
+  // slice's loads cost no vector address arithmetic.
+  const char* Ag = reinterpret_cast<const char*>(AL == 0 ? g.A + (int64_t)m0 * g.lda + kbase : g.A + kbase * g.lda + m0);
+  const char* Bg = reinterpret_cast<const char*>(BL == 1 ? g.B + (int64_t)n0 * g.ldb + kbase : g.B + kbase * g.ldb + n0);
+  constexpr int A_CPR = AL == 0 ? 8 : BM / 8;   // 16-byte chunks per tile row as it lies in memory
+  constexpr int B_CPR = BL == 1 ? 8 : BN / 8;
+  constexpr int A_RPC = 256 / A_CPR, B_RPC = 256 / B_CPR;  // tile rows covered by 256 lanes
+  // Lanes 8q..8q+7 move one 128-byte row piece.  For contraction-contiguous tiles (144-byte LDS
+  // rows) neighbouring lane groups take rows r and r+8, whose LDS images lie 32 banks apart, so
+  // the 16 lanes of one LDS write cycle touch all 64 banks once.
+  auto tile_row = [](int q) { return (q & ~15) | ((q & 15) >> 1) | ((q & 1) << 3); };
+  const int a_row = AL == 0 ? tile_row(tid / A_CPR) : tid / A_CPR;
+  const int b_row = BL == 1 ? tile_row(tid / B_CPR) : tid / B_CPR;
+  const uint32_t a_goff = (uint32_t)(((int64_t)a_row * g.lda + (tid % A_CPR) * 8) * 2);
+  const uint32_t b_goff = (uint32_t)(((int64_t)b_row * g.ldb + (tid % B_CPR) * 8) * 2);
+  const int64_t a_chunk = (int64_t)A_RPC * g.lda * 2, b_chunk = (int64_t)B_RPC * g.ldb * 2;
+  const int64_t a_step = AL == 0 ? BK * 2 : (int64_t)BK * g.lda * 2;
+  const int64_t b_step = BL == 1 ? BK * 2 : (int64_t)BK * g.ldb * 2;
+  const int a_soff = a_row * TL::A_STRIDE + (tid % A_CPR) * 16;
+  const int b_soff = b_row * TL::B_STRIDE + (tid % B_CPR) * 16;
 
-  u32x4 ra[TL::A_CHUNKS], rb[TL::B_CHUNKS];
+  // NBUF == 3: one LDS buffer like NBUF == 1, but two register sets, so that the loads of
+  // slice kt+2 are in flight while slice kt is multiplied (memory latency spans two slices).
+  constexpr int NSET = NBUF == 3 ? 2 : 1;
+  u32x4 ra[NSET][TL::A_CHUNKS], rb[NSET][TL::B_CHUNKS];
 
-  auto load_global = [&](int kt) {
+  auto load_global = [&](int kt, u32x4 (&ra)[TL::A_CHUNKS], u32x4 (&rb)[TL::B_CHUNKS]) {
+    const char* ap = Ag + kt * a_step;
+    const char* bp = Bg + kt * b_step;
 #pragma unroll
-    for (int i = 0; i < TL::A_CHUNKS; i++) {
-      int c = tid + i * 256;
-      const bf16* p;
-      if (AL == 0) p = Ag + (int64_t)(c >> 3) * g.lda + kt * BK + (c & 7) * 8;
-      else p = Ag + (int64_t)(kt * BK + c / (BM / 8)) * g.lda + (c % (BM / 8)) * 8;
-      ra[i] = *reinterpret_cast<const u32x4*>(p);
-    }
+    for (int i = 0; i < TL::A_CHUNKS; i++) ra[i] = *reinterpret_cast<const u32x4*>(ap + i * a_chunk + a_goff);
 #pragma unroll
-    for (int i = 0; i < TL::B_CHUNKS; i++) {
-      int c = tid + i * 256;
-      const bf16* p;
-      if (BL == 1) p = Bg + (int64_t)(c >> 3) * g.ldb + kt * BK + (c & 7) * 8;
-      else p = Bg + (int64_t)(kt * BK + c / (BN / 8)) * g.ldb + (c % (BN / 8)) * 8;
-      rb[i] = *reinterpret_cast<const u32x4*>(p);
-    }
+    for (int i = 0; i < TL::B_CHUNKS; i++) rb[i] = *reinterpret_cast<const u32x4*>(bp + i * b_chunk + b_goff);
   };
-  auto store_lds = [&](int buf) {
+  auto store_lds = [&](int buf, const u32x4 (&ra)[TL::A_CHUNKS], const u32x4 (&rb)[TL::B_CHUNKS]) {
     char* As = smem + buf * TL::STAGE;
     char* Bs = As + TL::A_BYTES;
 #pragma unroll
-    for (int i = 0; i < TL::A_CHUNKS; i++) {
-      int c = tid + i * 256;
-      int off = AL == 0 ? (c >> 3) * TL::A_STRIDE + (c & 7) * 16
-                        : (c / (BM / 8)) * TL::A_STRIDE + (c % (BM / 8)) * 16;
-      *reinterpret_cast<u32x4*>(As + off) = ra[i];
-    }
+    for (int i = 0; i < TL::A_CHUNKS; i++) *reinterpret_cast<u32x4*>(As + a_soff + i * (A_RPC * TL::A_STRIDE)) = ra[i];
 #pragma unroll
-    for (int i = 0; i < TL::B_CHUNKS; i++) {
-      int c = tid + i * 256;
-      int off = BL == 1 ? (c >> 3) * TL::B_STRIDE + (c & 7) * 16
-                        : (c / (BN / 8)) * TL::B_STRIDE + (c % (BN / 8)) * 16;
-      *reinterpret_cast<u32x4*>(Bs + off) = rb[i];
-    }
+    for (int i = 0; i < TL::B_CHUNKS; i++) *reinterpret_cast<u32x4*>(Bs + b_soff + i * (B_RPC * TL::B_STRIDE)) = rb[i];
   };
 
   f32x16 acc[TM][TN];
@@ -199,52 +203,63 @@ __global__ __launch_bounds__(256, OCC) void gemm_mfma_kernel(MfmaArgs g) {
     }
   };
   auto compute = [&](const char* As, const char* Bs) {
-    bf16x8 af[2][TM], bfr[2][TN];
-    read_frags(As, Bs, 0, af[0], bfr[0]);
+    // Scheduling fences keep the order written here: the LDS reads of a 16-wide step are issued
+    // DIST steps ahead of its MFMAs, so the MFMAs wait (by count) only for reads issued that
+    // long ago and the LDS latency hides behind whole steps of MFMAs.
+    constexpr int NS = BK / 16;
+    constexpr int DIST = TM * TN <= 4 ? 2 : 1;   // small sub-tiles have short steps: look further ahead
+    bf16x8 af[DIST + 1][TM], bfr[DIST + 1][TN];
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; kk++) {
-      if (kk + 1 < BK / 16) read_frags(As, Bs, kk + 1, af[(kk + 1) & 1], bfr[(kk + 1) & 1]);
+    for (int p = 0; p < DIST; p++) read_frags(As, Bs, p, af[p], bfr[p]);
+#pragma unroll
+    for (int kk = 0; kk < NS; kk++) {
+      if (kk + DIST < NS) read_frags(As, Bs, kk + DIST, af[(kk + DIST) % (DIST + 1)], bfr[(kk + DIST) % (DIST + 1)]);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < TM; i++)
 #pragma unroll
         for (int j = 0; j < TN; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
-      if (kk + 1 < BK / 16) {
-        constexpr int NREAD = (AL == 0 ? TM : 2 * TM) + (BL == 1 ? TN : 2 * TN);
-        constexpr int PER = (TM * TN) / NREAD > 0 ? (TM * TN) / NREAD : 1;
-#pragma unroll
-        for (int r = 0; r < NREAD; r++) {
-          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    // one LDS read
-          __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);  // a few MFMAs
-        }
-      }
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk % (DIST + 1)][j], af[kk % (DIST + 1)][i], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
   const int nk = g.K / BK;
-  load_global(0);
   if (NBUF == 2) {
-    store_lds(0);
+    load_global(0, ra[0], rb[0]);
+    store_lds(0, ra[0], rb[0]);
     __syncthreads();
     for (int kt = 0; kt < nk; kt++) {
-      if (kt + 1 < nk) load_global(kt + 1);
+      if (kt + 1 < nk) load_global(kt + 1, ra[0], rb[0]);
       const char* As = smem + (kt & 1) * TL::STAGE;
       compute(As, As + TL::A_BYTES);
-      if (kt + 1 < nk) store_lds((kt + 1) & 1);
+      if (kt + 1 < nk) store_lds((kt + 1) & 1, ra[0], rb[0]);
       __syncthreads();
     }
   } else {
-    for (int kt = 0; kt < nk; kt++) {
-      store_lds(0);
+    auto slice = [&](int kt, u32x4 (&sa)[TL::A_CHUNKS], u32x4 (&sb)[TL::B_CHUNKS]) {
+      store_lds(0, sa, sb);
       __syncthreads();
-      if (kt + 1 < nk) load_global(kt + 1);
+      if (kt + NSET < nk) load_global(kt + NSET, sa, sb);
       compute(smem, smem + TL::A_BYTES);
       __syncthreads();
+    };
+    load_global(0, ra[0], rb[0]);
+    if (NSET == 2) {
+      if (nk > 1) load_global(1, ra[1], rb[1]);
+      int kt = 0;
+      for (; kt + 1 < nk; kt += 2) {
+        slice(kt, ra[0], rb[0]);
+        slice(kt + 1, ra[NSET - 1], rb[NSET - 1]);
+      }
+      if (kt < nk) slice(kt, ra[0], rb[0]);
+    } else {
+      for (int kt = 0; kt < nk; kt++) slice(kt, ra[0], rb[0]);
     }
   }
 
   // Epilogue.  Each wavefront stages its sub-tile through LDS, 32 rows at a time (fp32, row
-  // pitch padded by 32 bytes), and reads it back so that the lanes of one store instruction
+  // pitch padded by 16 bytes), and reads it back so that the lanes of one store instruction
   // cover whole row segments, 16 bytes per lane: every global access of the epilogue (residual
   // and saved-derivative reads, outputs) is then fully coalesced.  (Storing straight from the
   // accumulator layout gives 8- or 16-byte pieces in 32 different rows per instruction;
@@ -252,7 +267,7 @@ __global__ __launch_bounds__(256, OCC) void gemm_mfma_kernel(MfmaArgs g) {
   TO* C = reinterpret_cast<TO*>(g.C);
   if (SPLIT) C += (int64_t)zsplit * g.split_stride;
   __syncthreads();  // every wave is done with the operand tiles
-  constexpr int PITCH = WN * 4 + 32;
+  constexpr int PITCH = WN * 4 + 16;  // rows 4 banks apart: 16-byte accesses of 16 rows, or of two row halves, never collide
   static_assert(4 * 32 * PITCH <= TL::LDS_BYTES, "epilogue staging must fit the operand buffers");
   char* stg = smem + wave * (32 * PITCH);
   constexpr int CPL = sizeof(TO) == 2 ? 8 : 4;  // consecutive columns per lane
@@ -346,7 +361,7 @@ int launch(const MfmaArgs& a, int nsplit, hipStream_t st) {
   bool prof = false;
   if (g_prof_on) {
     std::lock_guard<std::mutex> lk(g_prof_mu);
-    if (g_prof_on && hipEventCreate(&rec.e0) == hipSuccess) {
+    if (g_prof_on && (g_prof_count++ % (unsigned)g_prof_every) == 0 && hipEventCreate(&rec.e0) == hipSuccess) {
       if (hipEventCreate(&rec.e1) == hipSuccess) prof = true;
       else (void)hipEventDestroy(rec.e0);
     }
@@ -396,8 +411,9 @@ bool gemm_mfma_supported(const GemmDesc& g) {
   do {                                                                                                     \
     if (bm == 256 && bn == 256) return launch<256, 256, AL, BL, EPI, TO, SPLIT, 2, 1>(a, nsplit, st);      \
     if (bm == 256 && bn == 128 && nbuf == 2) return launch<256, 128, AL, BL, EPI, TO, SPLIT, 2, 1>(a, nsplit, st); \
-    if (bm == 256 && bn == 128) return launch<256, 128, AL, BL, EPI, TO, SPLIT, 1, 2>(a, nsplit, st);      \
+    if (bm == 256 && bn == 128 && nbuf == 1) return launch<256, 128, AL, BL, EPI, TO, SPLIT, 1, 2>(a, nsplit, st);      \
     if (nbuf == 2) return launch<128, 128, AL, BL, EPI, TO, SPLIT, 2, 2>(a, nsplit, st);                   \
+    if (nbuf == 3) return launch<128, 128, AL, BL, EPI, TO, SPLIT, 3, 2>(a, nsplit, st);                   \
     return launch<128, 128, AL, BL, EPI, TO, SPLIT, 1, 3>(a, nsplit, st);                                  \
   } while (0)
 
@@ -421,16 +437,17 @@ static int g_force_bm = 0, g_force_bn = 0, g_force_nbuf = 0;  // tuning override
 
 int gemm_mfma(const GemmDesc& g, hipStream_t st) {
   if (!gemm_mfma_supported(g)) return set_error(ALS_ERR_INVALID, "gemm_mfma: unsupported shape or layout");
-  // Tile choice (measured on MI355X with the real epilogues): the single-buffered 128x128
-  // variant, 3 workgroups per CU so that one's prologue/epilogue hides behind another's MFMAs,
-  // wins on this path's shapes (short K, tall M); 256x128 only for very wide outputs (the LM
-  // head and its weight gradient).
+  // Tile choice (measured on MI355X): the single-buffered 128x128 variant, 3 workgroups per CU
+  // so that one's prologue/epilogue hides behind another's MFMAs, for short K and few tiles;
+  // the double-buffered one once K is long enough to amortise its single resident pair;
+  // 256x128 (less operand traffic per flop) when there are enough tiles to fill the chip.
   int bm = 128, bn = 128, nbuf = 1;
   if (g_force_bm && fits(g.M, g.N, g_force_bm, g_force_bn)) { bm = g_force_bm; bn = g_force_bn; nbuf = g_force_nbuf; }
   else if (g.a_layout == 1) {
     if (fits(g.M, g.N, 256, 128) && (g.M / 256) * (g.N / 128) >= 128) { bm = 256; bn = 128; nbuf = 1; }
     else nbuf = 2;
-  } else if (fits(g.M, g.N, 256, 128) && (g.M / 256) * (g.N / 128) >= 2048) { bm = 256; bn = 128; }
+  } else if (fits(g.M, g.N, 256, 128) && (g.M / 256) * (g.N / 128) >= 1024) { bm = 256; bn = 128; }
+  else if (g.K >= 2048) nbuf = 2;
   MfmaArgs a;
   a.A = (const bf16*)g.A; a.B = (const bf16*)g.B; a.lda = g.lda; a.ldb = g.ldb;
   a.M = g.M; a.N = g.N; a.K = g.K; a.tiles_m = g.M / bm; a.tiles_n = g.N / bn;
@@ -471,6 +488,8 @@ int gemm_mfma(const GemmDesc& g, hipStream_t st) {
 extern "C" int als_prof_enable(int on) {
   std::lock_guard<std::mutex> lk(als::g_prof_mu);
   als::g_prof_on = on != 0;
+  als::g_prof_every = on > 1 ? on : 1;
+  als::g_prof_count = 0;
   return ALS_OK;
 }
 
@@ -503,8 +522,8 @@ extern "C" int als_prof_collect(int max_entries, int32_t* ids, int64_t* launches
 extern "C" int als_prof_kernel_name(int id, char* out, int out_len) {
   if (!out || out_len < 1) return als::set_error(ALS_ERR_INVALID, "als_prof_kernel_name: null output");
   static const char* epi[4] = {"STORE", "RESID", "GELU", "DGELU"};
-  int nbuf = ((id >> 8) & 1) + 1, bm = ((id & 1) + 1) * 128, bn = (((id >> 1) & 1) + 1) * 128;
-  int occ = nbuf == 2 ? (bm == 128 ? 2 : 1) : (bm == 256 ? 2 : 3);
+  int nbuf = ((id >> 8) & 3) + 1, bm = ((id & 1) + 1) * 128, bn = (((id >> 1) & 1) + 1) * 128;
+  int occ = nbuf == 2 ? (bm == 128 ? 2 : 1) : nbuf == 3 ? 2 : (bm == 256 ? 2 : 3);
   snprintf(out, out_len, "gemm_mfma_kernel<%d, %d, %d, %d, %s, %s, %s, %d, %d>", bm, bn, (id >> 2) & 1, (id >> 3) & 1,
            epi[(id >> 4) & 3], (id >> 6) & 1 ? "bf16" : "float", (id >> 7) & 1 ? "true" : "false", nbuf, occ);
   return ALS_OK;
@@ -514,7 +533,7 @@ extern "C" int als_prof_kernel_name(int id, char* out, int out_len) {
 // (2 = double, 1 = single buffer with more workgroups per CU); 0,0 restores the automatic choice.  Not thread-safe; meant for benchmarks.
 extern "C" int als_k_set_gemm_tile(int bm, int bn, int nbuf) {
   bool ok = (bm == 0 && bn == 0) || (bm == 256 && bn == 256) || (bm == 256 && bn == 128) || (bm == 128 && bn == 128);
-  if (!ok || (bm && nbuf != 1 && nbuf != 2)) return als::set_error(ALS_ERR_INVALID, "unsupported tile %dx%d/%d", bm, bn, nbuf);
+  if (!ok || (bm && nbuf != 1 && nbuf != 2 && !(nbuf == 3 && bm == 128))) return als::set_error(ALS_ERR_INVALID, "unsupported tile %dx%d/%d", bm, bn, nbuf);
   als::g_force_bm = bm; als::g_force_bn = bn; als::g_force_nbuf = nbuf;
   return ALS_OK;
 }
