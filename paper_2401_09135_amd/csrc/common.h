@@ -95,8 +95,9 @@ int mean_rows(const float* loss_row, float* out, int T, hipStream_t st);
 // [n_steps][V+1], rank and pos are [n_steps][B*S].
 int embed_sort(const int32_t* tok, int n_steps, int B, int S, int V, int32_t* offset, int32_t* rank,
                int32_t* pos, hipStream_t st);
-int embed_bwd(const int32_t* offset, const int32_t* pos, const float* dx, float* dE, float* dPpos,
-              int B, int S, int d, int V, hipStream_t st);
+// scratch: 2 * ceil(B*S / 32) * d floats (partial rows of position lists that cross 32-position chunks)
+int embed_bwd(const int32_t* tok, const int32_t* offset, const int32_t* pos, const float* dx, float* dE,
+              float* dPpos, float* scratch, int B, int S, int d, int V, hipStream_t st);
 int cast_copy(const float* src, void* dst, int64_t n, int dst_bf16, hipStream_t st);
 
 struct AdamArgs {

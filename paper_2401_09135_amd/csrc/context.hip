@@ -157,7 +157,7 @@ int forward(als_ctx* c, Worker& w, const int32_t* tok, float* loss_out) {
   return ALS_OK;
 }
 
-int backward(als_ctx* c, Worker& w, int slot) {
+int backward(als_ctx* c, Worker& w, const int32_t* tok, int slot) {
   const als_config& g = c->cfg;
   const Layout& L = c->L;
   hipStream_t st = w.stream;
@@ -192,8 +192,9 @@ int backward(als_ctx* c, Worker& w, int slot) {
     RUN(rmsnorm_bwd(w.dtmp, w.x[l], w.rstd1[l], w.theta + L.g1[l], w.dxb, w.dxa, w.dx_lp, c->bf,
                     w.grad + L.g1[l], w.partial, T, d, st));
   }
-  RUN(embed_bwd(w.sort_offset + (int64_t)slot * (V + 1), w.sort_pos + (int64_t)slot * T, w.dxa,
-                w.grad + L.E, w.grad + L.Ppos, B, S, d, V, st));
+  // w.dtmp (T x d floats) is free again here: scratch for the embedding gradient's chunk partials
+  RUN(embed_bwd(tok, w.sort_offset + (int64_t)slot * (V + 1), w.sort_pos + (int64_t)slot * T, w.dxa,
+                w.grad + L.E, w.grad + L.Ppos, w.dtmp, B, S, d, V, st));
   return ALS_OK;
 }
 
@@ -304,7 +305,7 @@ extern "C" int als_worker_local_steps(als_ctx* ctx, int worker, int n_steps, con
   for (int s = 0; s < n_steps; s++) {
     const int32_t* tok = tokens + (int64_t)s * per;
     RUN(forward(ctx, w, tok, w.losses_dev + s));
-    RUN(backward(ctx, w, s));
+    RUN(backward(ctx, w, tok, s));
     w.adam_n += 1;
     AdamArgs a;
     a.lr = lr_host[s];
@@ -334,7 +335,7 @@ extern "C" int als_worker_loss_grad(als_ctx* ctx, int worker, const int32_t* tok
   RUN(embed_sort(tokens, 1, ctx->cfg.batch, ctx->cfg.seq_len, ctx->cfg.vocab, w.sort_offset, w.sort_rank,
                  w.sort_pos, w.stream));
   RUN(forward(ctx, w, tokens, w.losses_dev));
-  RUN(backward(ctx, w, 0));
+  RUN(backward(ctx, w, tokens, 0));
   ALS_HIP(hipMemcpyAsync(w.losses_host, w.losses_dev, 4, hipMemcpyDeviceToHost, w.stream));
   ALS_HIP(hipEventRecord(w.done_ev, w.stream));
   ALS_HIP(hipStreamSynchronize(w.stream));

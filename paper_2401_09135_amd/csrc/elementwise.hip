@@ -335,9 +335,8 @@ int embed_fwd(const int32_t* tok, const float* E, const float* Ppos, float* x, i
 //     counting sort whose ranks are fixed by position order: offset[v] .. offset[v+1] delimit
 //     the positions holding token v inside pos[].  It depends on the tokens only, so one
 //     launch prepares every step of a local round.
-// (2) embed_bwd_rows: one workgroup per vocabulary row adds the dx rows of its positions
-//     (wave w of 16 takes every 16th position, the partial rows are added in a fixed order)
-//     and writes the row, zeros included.
+// (2) embed_bwd: a pass over 32-position chunks of that list and a pass over vocabulary rows
+//     (described at the kernels below).
 // dPpos[s,:] = sum_b dx[b,s,:] in batch order.
 __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
 #pragma unroll
@@ -414,87 +413,127 @@ int embed_sort(const int32_t* tok, int n_steps, int B, int S, int V, int32_t* of
   return ALS_OK;
 }
 
-#define EMB_MAXD4 4  // float4 slots per lane: d <= 1024
-template <int NW>
-__global__ __launch_bounds__(64 * NW) void embed_bwd_rows_kernel(const int32_t* __restrict__ offset,
-                                                                 const int32_t* __restrict__ pos,
-                                                                 const float* __restrict__ dx,
-                                                                 float* __restrict__ dE, int d) {
-  extern __shared__ float smem[];  // [NW][d]
-  const int v = blockIdx.x, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int beg = offset[v], end = offset[v + 1];
+// dE from the sorted position list, in two passes that never leave a long list to one block:
+//   chunks: block c walks sorted positions [32 c, 32 c + 32), 8 row loads in flight, adding the
+//     rows of equal tokens in list order.  A token whose whole list lies in this chunk is written
+//     to dE at once; a list that continues into the next chunk leaves its part in scratch slot
+//     (c, 1); one that began in an earlier chunk leaves its part in slot (c, 0).
+//   rows: one wavefront per vocabulary row: zeros for a token that does not occur, nothing for a
+//     list inside one chunk, else slot (first, 1) + slots (first+1 .. last, 0) in chunk order.
+// Every sum has a fixed order, so the result does not depend on scheduling.
+constexpr int EMB_CH = 32;
+#define EMB_MAXD4 4  // float4 slots per lane in the row pass: d <= 1024
+
+__global__ __launch_bounds__(128) void embed_bwd_chunks_kernel(
+    const int32_t* __restrict__ tok, const int32_t* __restrict__ offset, const int32_t* __restrict__ pos,
+    const float* __restrict__ dx, float* __restrict__ dE, float* __restrict__ scratch, int T, int S, int V, int d) {
+  __shared__ int s_pos[EMB_CH], s_tok[EMB_CH];
+  const int c = blockIdx.x, i0 = c * EMB_CH, tid = threadIdx.x;
+  const int n = T - i0 < EMB_CH ? T - i0 : EMB_CH;
   const int d4 = d / 4;
-  float4* out = reinterpret_cast<float4*>(dE + (int64_t)v * d);
-  if (beg == end) {
-    for (int c = threadIdx.x; c < d4; c += 64 * NW) out[c] = make_float4(0.f, 0.f, 0.f, 0.f);
-    return;
-  }
-  if (end - beg == 1) {  // a single position: copy its row
-    const float4* row = reinterpret_cast<const float4*>(dx + (int64_t)pos[beg] * d);
-    for (int c = threadIdx.x; c < d4; c += 64 * NW) out[c] = row[c];
-    return;
-  }
-  float4 acc[EMB_MAXD4];
-#pragma unroll
-  for (int s = 0; s < EMB_MAXD4; s++) acc[s] = make_float4(0.f, 0.f, 0.f, 0.f);
-  // A wave takes every NW-th position of the row's list, UNR of them in flight at a time (the
-  // few very frequent tokens have thousands of positions: the loop is bound by load latency);
-  // they are added in list order whatever UNR is.
-  constexpr int UNR = 8;
-  for (int r0 = beg + w; r0 < end; r0 += NW * UNR) {
-    float4 x[UNR][EMB_MAXD4];
-#pragma unroll
-    for (int u = 0; u < UNR; u++) {
-      int r = r0 + u * NW;
-      const float4* row = reinterpret_cast<const float4*>(dx + (int64_t)pos[r < end ? r : beg] * d);
-#pragma unroll
-      for (int s = 0; s < EMB_MAXD4; s++) {
-        int c = lane + 64 * s;
-        x[u][s] = (r < end && c < d4) ? row[c] : make_float4(0.f, 0.f, 0.f, 0.f);
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < UNR; u++)
-      if (r0 + u * NW < end) {
-#pragma unroll
-        for (int s = 0; s < EMB_MAXD4; s++) {
-          acc[s].x += x[u][s].x; acc[s].y += x[u][s].y; acc[s].z += x[u][s].z; acc[s].w += x[u][s].w;
-        }
-      }
-  }
-#pragma unroll
-  for (int s = 0; s < EMB_MAXD4; s++) {
-    int c = lane + 64 * s;
-    if (c < d4) reinterpret_cast<float4*>(smem + w * d)[c] = acc[s];
+  if (tid < n) {
+    int t = pos[i0 + tid];
+    int id = tok[(int64_t)(t / S) * (S + 1) + (t % S)];
+    s_pos[tid] = t;
+    s_tok[tid] = id < 0 ? 0 : (id >= V ? V - 1 : id);
   }
   __syncthreads();
-  for (int c = threadIdx.x; c < d; c += 64 * NW) {
-    float t = smem[c];
+  const float4* dx4 = reinterpret_cast<const float4*>(dx);
+  for (int col = tid; col < d4; col += 128) {   // one pass for d <= 512
+    auto flush = [&](int v, float4 acc) {
+      int beg = offset[v], end = offset[v + 1];
+      int cf = beg / EMB_CH, cl = (end - 1) / EMB_CH;
+      float4* dst = cf == cl ? reinterpret_cast<float4*>(dE) + (int64_t)v * d4
+                             : reinterpret_cast<float4*>(scratch) + (int64_t)(2 * c + (c == cf ? 1 : 0)) * d4;
+      dst[col] = acc;
+    };
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    int cur = s_tok[0];
+    for (int j0 = 0; j0 < n; j0 += 8) {
+      float4 x[8];
 #pragma unroll
-    for (int i = 1; i < NW; i++) t += smem[i * d + c];
-    dE[(int64_t)v * d + c] = t;
+      for (int u = 0; u < 8; u++) {
+        int j = j0 + u;
+        x[u] = j < n ? dx4[(int64_t)s_pos[j] * d4 + col] : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; u++) {
+        int j = j0 + u;
+        if (j < n) {
+          int tk = s_tok[j];
+          if (tk != cur) {  // block-uniform
+            flush(cur, acc);
+            acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            cur = tk;
+          }
+          acc.x += x[u].x; acc.y += x[u].y; acc.z += x[u].z; acc.w += x[u].w;
+        }
+      }
+    }
+    flush(cur, acc);
+  }
+}
+
+__global__ __launch_bounds__(256) void embed_bwd_rows_kernel(const int32_t* __restrict__ offset,
+                                                             const float* __restrict__ scratch,
+                                                             float* __restrict__ dE, int V, int d) {
+  const int lane = threadIdx.x & 63;
+  const int v = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (v >= V) return;
+  const int beg = offset[v], end = offset[v + 1];
+  const int d4 = d / 4;
+  float4* out = reinterpret_cast<float4*>(dE) + (int64_t)v * d4;
+  if (beg == end) {
+    for (int col = lane; col < d4; col += 64) out[col] = make_float4(0.f, 0.f, 0.f, 0.f);
+    return;
+  }
+  const int cf = beg / EMB_CH, cl = (end - 1) / EMB_CH;
+  if (cf == cl) return;  // written by the chunk pass
+  const float4* sc = reinterpret_cast<const float4*>(scratch);
+#pragma unroll
+  for (int s = 0; s < EMB_MAXD4; s++) {
+    int col = lane + 64 * s;
+    if (col >= d4) break;
+    float4 acc = sc[(int64_t)(2 * cf + 1) * d4 + col];
+#pragma unroll 8
+    for (int c = cf + 1; c <= cl; c++) {
+      float4 x = sc[(int64_t)(2 * c) * d4 + col];
+      acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
+    }
+    out[col] = acc;
   }
 }
 
 __global__ void embed_bwd_pos_kernel(const float* __restrict__ dx, float* __restrict__ dPpos,
                                      int B, int S, int d) {
   int s = blockIdx.x;
-  for (int c = threadIdx.x; c < d; c += blockDim.x) {
-    float acc = 0.0f;
-    for (int b = 0; b < B; b++) acc += dx[((int64_t)b * S + s) * d + c];
-    dPpos[(int64_t)s * d + c] = acc;
+  const int d4 = d / 4;
+  const float4* dx4 = reinterpret_cast<const float4*>(dx);
+  for (int c = threadIdx.x; c < d4; c += blockDim.x) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int b0 = 0; b0 < B; b0 += 8) {  // 8 loads in flight, added in batch order
+      float4 x[8];
+#pragma unroll
+      for (int u = 0; u < 8; u++)
+        x[u] = b0 + u < B ? dx4[((int64_t)(b0 + u) * S + s) * d4 + c] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int u = 0; u < 8; u++)
+        if (b0 + u < B) { acc.x += x[u].x; acc.y += x[u].y; acc.z += x[u].z; acc.w += x[u].w; }
+    }
+    reinterpret_cast<float4*>(dPpos)[(int64_t)s * d4 + c] = acc;
   }
 }
 
-int embed_bwd(const int32_t* offset, const int32_t* pos, const float* dx, float* dE, float* dPpos,
-              int B, int S, int d, int V, hipStream_t st) {
+int embed_bwd(const int32_t* tok, const int32_t* offset, const int32_t* pos, const float* dx, float* dE,
+              float* dPpos, float* scratch, int B, int S, int d, int V, hipStream_t st) {
   if (d > 256 * EMB_MAXD4 || d % 4) return set_error(ALS_ERR_INVALID, "embed_bwd: d unsupported");
-  // 16 wavefronts per vocabulary row so that the few very frequent tokens (Zipf) finish soon;
-  // [16][d] floats of LDS fit the default 64 KiB up to d = 1024
-  hipLaunchKernelGGL(embed_bwd_rows_kernel<16>, dim3(V), dim3(1024), (size_t)16 * d * sizeof(float), st,
-                     offset, pos, dx, dE, d);
+  const int T = B * S;
+  hipLaunchKernelGGL(embed_bwd_chunks_kernel, dim3((T + EMB_CH - 1) / EMB_CH), dim3(128), 0, st, tok, offset,
+                     pos, dx, dE, scratch, T, S, V, d);
   ALS_CHECK_LAUNCH();
-  int threads = d < 256 ? d : 256;
+  hipLaunchKernelGGL(embed_bwd_rows_kernel, dim3((V + 3) / 4), dim3(256), 0, st, offset, scratch, dE, V, d);
+  ALS_CHECK_LAUNCH();
+  int threads = d / 4 < 256 ? (d / 4 < 64 ? 64 : d / 4) : 256;
   hipLaunchKernelGGL(embed_bwd_pos_kernel, dim3(S), dim3(threads), 0, st, dx, dPpos, B, S, d);
   ALS_CHECK_LAUNCH();
   return ALS_OK;
@@ -624,22 +663,32 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(
     partial[(int64_t)blockIdx.x * d + c] = smem[c] + smem[d + c] + smem[2 * d + c] + smem[3 * d + c];
 }
 
-// out[c] = sum_b partial[b][c]: 32 columns per block, 8 row groups each adding every 8th
-// partial, combined in a fixed order.
-__global__ __launch_bounds__(256) void sum_partials_kernel(const float* __restrict__ partial,
-                                                           float* __restrict__ out, int nblk, int d) {
-  __shared__ float sh[8][33];
+// out[c] = sum_b partial[b][c]: 32 columns per block, 32 row groups each adding every 32nd
+// partial (8 independent loads in flight: the kernel is pure load latency), combined in a fixed
+// order.
+__global__ __launch_bounds__(1024) void sum_partials_kernel(const float* __restrict__ partial,
+                                                            float* __restrict__ out, int nblk, int d) {
+  __shared__ float sh[32][33];
   int cl = threadIdx.x & 31, rg = threadIdx.x >> 5;
   int c = blockIdx.x * 32 + cl;
   float acc = 0.0f;
   if (c < d)
-    for (int b = rg; b < nblk; b += 8) acc += partial[(int64_t)b * d + c];
+    for (int b0 = rg; b0 < nblk; b0 += 32 * 8) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; u++) {
+        int b = b0 + 32 * u;
+        v[u] = b < nblk ? partial[(int64_t)b * d + c] : 0.0f;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; u++) acc += v[u];
+    }
   sh[rg][cl] = acc;
   __syncthreads();
   if (rg == 0 && c < d) {
     float t = sh[0][cl];
 #pragma unroll
-    for (int r = 1; r < 8; r++) t += sh[r][cl];
+    for (int r = 1; r < 32; r++) t += sh[r][cl];
     out[c] = t;
   }
 }
@@ -662,7 +711,7 @@ int rmsnorm_bwd(const float* dy, const float* x, const float* rstd, const float*
     hipLaunchKernelGGL(rmsnorm_bwd_kernel<float>, dim3(nblk), dim3(256), sm, st, dy, x, rstd, g, dx_in,
                        dx_out, (float*)dx_lp, partial, T, d);
   ALS_CHECK_LAUNCH();
-  hipLaunchKernelGGL(sum_partials_kernel, dim3((d + 31) / 32), dim3(256), 0, st, partial, dg, nblk, d);
+  hipLaunchKernelGGL(sum_partials_kernel, dim3((d + 31) / 32), dim3(1024), 0, st, partial, dg, nblk, d);
   ALS_CHECK_LAUNCH();
   return ALS_OK;
 }
