@@ -51,12 +51,38 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& x, int kk) {
 }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
+// A use of fragments that were loaded from global memory before a loop: the compiler then waits
+// for those loads HERE.  Without it, it re-checks them inside the loop with a count that also
+// covers the loop's own freshly issued tile loads, i.e. every iteration waits for its prefetch.
+__device__ __forceinline__ void settle(const bf16x8 (&f)[4]) {
+  asm volatile("" ::"v"(f[0]), "v"(f[1]), "v"(f[2]), "v"(f[3]));
+}
 
 // byte offset of this lane's source address for a transposed A fragment inside a
 // [row][64] tile: block of 32 columns `cb`, 16-row group `rb` (rows rb .. rb+3 and rb+8 .. +11)
 __device__ __forceinline__ int tr_off(int lane, int rb, int cb) {
   int hf = lane >> 5;
   return (rb + 4 * hf + ((lane & 15) >> 2)) * ROW_D + (cb + 16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
+}
+
+// Workgroup -> (block along the sequence, head, sample).  Workgroup ids are dealt round-robin to
+// the 8 XCDs; with the sequence block as the fastest grid index every XCD would get blocks of
+// ONE causal position (all long or all short) and the chip would wait for two XCDs.  Instead
+// XCD x takes (head, sample) pairs x, x + 8, ... and runs all sequence blocks of a pair, longest
+// first: equal work per XCD, and the blocks that share K and V share an L2.
+struct BlockId { int blk, hd, b; };
+__device__ __forceinline__ BlockId block_id(int nblk, int h, int B) {
+  const int i = blockIdx.x, pairs = h * B;
+  int blk, pair;
+  if ((pairs & 7) == 0) {
+    const int j = i >> 3;
+    pair = (i & 7) + 8 * (j / nblk);
+    blk = j % nblk;
+  } else {
+    pair = i / nblk;
+    blk = i % nblk;
+  }
+  return {blk, pair % h, pair / h};
 }
 
 // copy a [64 rows][64] bf16 tile from global (row pitch ld elements) to registers / LDS
@@ -92,11 +118,12 @@ __device__ __forceinline__ void store_rows(bf16* dst, const f32x16 (&acc)[2], fl
 // ------------------------------------------------------------------------------------------
 // forward: one workgroup per (128 queries, head, sample); wave w owns 32 queries
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o,
-                                                       float* __restrict__ lse, int S, int h, float scale_log2) {
+__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ o,
+                                                       float* __restrict__ lse, int S, int h, int B, float scale_log2) {
   __shared__ __attribute__((aligned(16))) char smem[4 * TILE_BYTES];  // 2 stages x (K, V)
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, hf = lane >> 5;
-  const int q0 = (gridDim.x - 1 - blockIdx.x) * 128, hd = blockIdx.y, b = blockIdx.z;
+  const BlockId id = block_id(S / 128, h, B);
+  const int q0 = (S / 128 - 1 - id.blk) * 128, hd = id.hd, b = id.b;
   const int d = h * DH;
   const int64_t ld = 3 * (int64_t)d;
   const bf16* base = qkv + (int64_t)b * S * ld + hd * DH;
@@ -114,6 +141,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16* __restrict__ 
   tile_load(vr, base + 2 * d, ld, tid);
   tile_store(kr, smem, tid);
   tile_store(vr, smem + TILE_BYTES, tid);
+  settle(qf);
   __syncthreads();
   for (int jt = 0; jt < n_tiles; jt++) {
     const int key0 = jt * 64;
@@ -124,12 +152,31 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16* __restrict__ 
     const char* Ks = smem + (jt & 1) * 2 * TILE_BYTES;
     const char* Vs = Ks + TILE_BYTES;
     if (key0 <= qw + 31) {  // wave-uniform: some key of the tile is visible to some query
+      // The K fragment reads are issued together ahead of the score MFMAs, the V fragment reads
+      // right behind those MFMAs (scheduling fences keep that order): each MFMA waits only for
+      // its own operands, by count, and the V fragments arrive while the softmax runs.
+      bf16x8 kfr[2][4], vfr[2][2][2];
+#pragma unroll
+      for (int kk = 0; kk < 4; kk++)
+#pragma unroll
+        for (int kt = 0; kt < 2; kt++)
+          kfr[kt][kk] = lds_direct(Ks + (kt * 32 + (lane & 31)) * ROW_D + kk * 32 + hf * 16);
+      __builtin_amdgcn_sched_barrier(0);
       f32x16 s[2] = {zero16(), zero16()};
+#pragma unroll
+      for (int kk = 0; kk < 4; kk++)
+#pragma unroll
+        for (int kt = 0; kt < 2; kt++) s[kt] = MFMA(kfr[kt][kk], qf[kk], s[kt]);
 #pragma unroll
       for (int kt = 0; kt < 2; kt++)
 #pragma unroll
-        for (int kk = 0; kk < 4; kk++)
-          s[kt] = MFMA(lds_direct(Ks + (kt * 32 + (lane & 31)) * ROW_D + kk * 32 + hf * 16), qf[kk], s[kt]);
+        for (int kk = 0; kk < 2; kk++)
+#pragma unroll
+          for (int dt = 0; dt < 2; dt++) {
+            int off = tr_off(lane, kt * 32 + 16 * kk, dt * 32);
+            vfr[kt][kk][dt] = lds_tr2(Vs + off, Vs + off + 8 * ROW_D);
+          }
+      __builtin_amdgcn_sched_barrier(0);
       // running maximum in raw score units; probabilities are exp2((s - m) * scale_log2) with
       // the scale folded into one fma per element; masking only on tiles that cross the diagonal
       const bool need_mask = key0 + 63 > qw;
@@ -177,10 +224,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const bf16* __restrict__ 
         for (int kk = 0; kk < 2; kk++) {
           bf16x8 pf = pack8(s[kt], kk);
 #pragma unroll
-          for (int dt = 0; dt < 2; dt++) {
-            int off = tr_off(lane, kt * 32 + 16 * kk, dt * 32);
-            oacc[dt] = MFMA(lds_tr2(Vs + off, Vs + off + 8 * ROW_D), pf, oacc[dt]);
-          }
+          for (int dt = 0; dt < 2; dt++) oacc[dt] = MFMA(vfr[kt][kk][dt], pf, oacc[dt]);
         }
     }
     if (jt + 1 < n_tiles) {
@@ -221,12 +265,13 @@ __global__ __launch_bounds__(256) void attn_bwd_rowdot_kernel(const bf16* __rest
 // backward, dQ: one workgroup per (128 queries, head, sample).  Per 64-key tile:
 //   S^T = K Q^T ; dP^T = V dO^T ; dS^T = P^T (dP^T - D) ; dQ^T += K^T dS^T
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ d_o,
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ d_o,
                                                           const float* __restrict__ lse, const float* __restrict__ D,
-                                                          bf16* __restrict__ dqkv, int S, int h, float scale) {
+                                                          bf16* __restrict__ dqkv, int S, int h, int B, float scale) {
   __shared__ __attribute__((aligned(16))) char smem[4 * TILE_BYTES];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, hf = lane >> 5;
-  const int q0 = (gridDim.x - 1 - blockIdx.x) * 128, hd = blockIdx.y, b = blockIdx.z;
+  const BlockId id = block_id(S / 128, h, B);
+  const int q0 = (S / 128 - 1 - id.blk) * 128, hd = id.hd, b = id.b;
   const int d = h * DH;
   const int64_t ld = 3 * (int64_t)d;
   const bf16* base = qkv + (int64_t)b * S * ld + hd * DH;
@@ -250,6 +295,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16* __restrict
   tile_load(vr, base + 2 * d, ld, tid);
   tile_store(kr, smem, tid);
   tile_store(vr, smem + TILE_BYTES, tid);
+  settle(qf);
+  settle(gf);
+  asm volatile("" ::"v"(lse2), "v"(Dq));
   __syncthreads();
   for (int jt = 0; jt < n_tiles; jt++) {
     const int key0 = jt * 64;
@@ -265,11 +313,28 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16* __restrict
       for (int kt = 0; kt < 2; kt++) {
         f32x16 s = zero16(), dp = zero16();
         const int roff = (kt * 32 + (lane & 31)) * ROW_D + hf * 16;
+        // fragment reads ahead of their MFMAs, the transposed K reads behind the score MFMAs
+        // (scheduling fences keep the order; see the forward kernel)
+        bf16x8 kfr[4], vfr[4], ktr[2][2];
 #pragma unroll
         for (int kk = 0; kk < 4; kk++) {
-          s = MFMA(lds_direct(Ks + roff + kk * 32), qf[kk], s);
-          dp = MFMA(lds_direct(Vs + roff + kk * 32), gf[kk], dp);
+          kfr[kk] = lds_direct(Ks + roff + kk * 32);
+          vfr[kk] = lds_direct(Vs + roff + kk * 32);
         }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kk = 0; kk < 4; kk++) {
+          s = MFMA(kfr[kk], qf[kk], s);
+          dp = MFMA(vfr[kk], gf[kk], dp);
+        }
+#pragma unroll
+        for (int kk = 0; kk < 2; kk++)
+#pragma unroll
+          for (int dt = 0; dt < 2; dt++) {
+            int off = tr_off(lane, kt * 32 + 16 * kk, dt * 32);
+            ktr[kk][dt] = lds_tr2(Ks + off, Ks + off + 8 * ROW_D);
+          }
+        __builtin_amdgcn_sched_barrier(0);
         if (need_mask) {
 #pragma unroll
           for (int v = 0; v < 16; v++) {
@@ -286,10 +351,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16* __restrict
         for (int kk = 0; kk < 2; kk++) {
           bf16x8 dsf = pack8(s, kk);
 #pragma unroll
-          for (int dt = 0; dt < 2; dt++) {
-            int off = tr_off(lane, kt * 32 + 16 * kk, dt * 32);
-            dq[dt] = MFMA(lds_tr2(Ks + off, Ks + off + 8 * ROW_D), dsf, dq[dt]);
-          }
+          for (int dt = 0; dt < 2; dt++) dq[dt] = MFMA(ktr[kk][dt], dsf, dq[dt]);
         }
       }
     }
@@ -310,12 +372,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const bf16* __restrict
 //   dV^T += dO^T P ; dK^T += Q^T dS
 // ------------------------------------------------------------------------------------------
 template <int KT>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ d_o,
+__global__ __launch_bounds__(256, KT == 1 ? 2 : 1) void attn_bwd_dkv_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ d_o,
                                                            const float* __restrict__ lse, const float* __restrict__ D,
-                                                           bf16* __restrict__ dqkv, int S, int h, float scale) {
-  __shared__ __attribute__((aligned(16))) char smem[4 * TILE_BYTES];  // 2 stages x (Q, dO)
+                                                           bf16* __restrict__ dqkv, int S, int h, int B, float scale) {
+  // 2 stages x (Q, dO) tiles, then 2 stages x (64 log-sum-exp values, 64 row dots)
+  __shared__ __attribute__((aligned(16))) char smem[4 * TILE_BYTES + 2 * 512];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, hf = lane >> 5;
-  const int kb0 = blockIdx.x * (128 * KT), hd = blockIdx.y, b = blockIdx.z;
+  const BlockId id = block_id(S / (128 * KT), h, B);  // key block 0 (all queries see it) first
+  const int kb0 = id.blk * (128 * KT), hd = id.hd, b = id.b;
   const int d = h * DH;
   const int64_t ld = 3 * (int64_t)d;
   const bf16* base = qkv + (int64_t)b * S * ld + hd * DH;
@@ -344,19 +408,32 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16* __restric
   const int qstart = (kb0 / 64) * 64;
   const int n_tiles = (S - qstart) / 64;
   TileRegs qr, gr;
+  float4 st4 = make_float4(0.f, 0.f, 0.f, 0.f);  // lanes 0-15: 4 lse values, lanes 16-31: 4 row dots
+  auto stats_load = [&](int q_first) {
+    if (tid < 32) st4 = *reinterpret_cast<const float4*>((tid < 16 ? lse_b : D_b) + q_first + 4 * (tid & 15));
+  };
+  auto stats_store = [&](int stage) {
+    if (tid < 32) *reinterpret_cast<float4*>(smem + 4 * TILE_BYTES + stage * 512 + tid * 16) = st4;
+  };
   tile_load(qr, base + (int64_t)qstart * ld, ld, tid);
   tile_load(gr, dobase + (int64_t)qstart * d, d, tid);
+  stats_load(qstart);
   tile_store(qr, smem, tid);
   tile_store(gr, smem + TILE_BYTES, tid);
+  stats_store(0);
+#pragma unroll
+  for (int kt = 0; kt < KT; kt++) { settle(kf[kt]); settle(vf[kt]); }
   __syncthreads();
   for (int it = 0; it < n_tiles; it++) {
     const int qt0 = qstart + it * 64;
     if (it + 1 < n_tiles) {
       tile_load(qr, base + (int64_t)(qt0 + 64) * ld, ld, tid);
       tile_load(gr, dobase + (int64_t)(qt0 + 64) * d, d, tid);
+      stats_load(qt0 + 64);
     }
     const char* Qs = smem + (it & 1) * 2 * TILE_BYTES;
     const char* Gs = Qs + TILE_BYTES;
+    const char* Ss = smem + 4 * TILE_BYTES + (it & 1) * 512;
 #pragma unroll
     for (int qh = 0; qh < 2; qh++) {
       const int qs = qt0 + qh * 32;          // first query of this half tile
@@ -365,8 +442,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16* __restric
       float4 l4[4], d4[4];
 #pragma unroll
       for (int g = 0; g < 4; g++) {
-        l4[g] = *reinterpret_cast<const float4*>(lse_b + qs + 8 * g + 4 * hf);
-        d4[g] = *reinterpret_cast<const float4*>(D_b + qs + 8 * g + 4 * hf);
+        l4[g] = *reinterpret_cast<const float4*>(Ss + (qh * 32 + 8 * g + 4 * hf) * 4);
+        d4[g] = *reinterpret_cast<const float4*>(Ss + 256 + (qh * 32 + 8 * g + 4 * hf) * 4);
         l4[g].x *= -LOG2E; l4[g].y *= -LOG2E; l4[g].z *= -LOG2E; l4[g].w *= -LOG2E;
       }
       const int roff = (qh * 32 + (lane & 31)) * ROW_D + hf * 16;
@@ -423,6 +500,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const bf16* __restric
       char* nxt = smem + ((it + 1) & 1) * 2 * TILE_BYTES;
       tile_store(qr, nxt, tid);
       tile_store(gr, nxt + TILE_BYTES, tid);
+      stats_store((it + 1) & 1);
     }
     __syncthreads();
   }
@@ -441,7 +519,7 @@ bool attention_mfma_supported(int S, int dh, int bf) { return bf && dh == 64 && 
 int attention_fwd_mfma(const void* qkv, void* o, float* lse, int B, int S, int h, int dh, hipStream_t st) {
   if (!attention_mfma_supported(S, dh, 1) || B < 1 || h < 1) return set_error(ALS_ERR_INVALID, "attention_fwd_mfma: unsupported shape");
   float scale_log2 = (1.0f / sqrtf((float)dh)) * LOG2E;
-  hipLaunchKernelGGL(attn_fwd_kernel, dim3(S / 128, h, B), dim3(256), 0, st, (const bf16*)qkv, (bf16*)o, lse, S, h, scale_log2);
+  hipLaunchKernelGGL(attn_fwd_kernel, dim3(S / 128 * h * B), dim3(256), 0, st, (const bf16*)qkv, (bf16*)o, lse, S, h, B, scale_log2);
   ALS_CHECK_LAUNCH();
   return ALS_OK;
 }
@@ -454,15 +532,13 @@ int attention_bwd_mfma(const void* qkv, const void* o, const void* d_o, const fl
   hipLaunchKernelGGL(attn_bwd_rowdot_kernel, dim3((unsigned)((n_pairs * 8 + 255) / 256)), dim3(256), 0, st,
                      (const bf16*)o, (const bf16*)d_o, dscratch, S, h, n_pairs);
   ALS_CHECK_LAUNCH();
-  hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(S / 128, h, B), dim3(256), 0, st, (const bf16*)qkv, (const bf16*)d_o,
-                     lse, dscratch, (bf16*)dqkv, S, h, scale);
+  hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(S / 128 * h * B), dim3(256), 0, st, (const bf16*)qkv, (const bf16*)d_o,
+                     lse, dscratch, (bf16*)dqkv, S, h, B, scale);
   ALS_CHECK_LAUNCH();
-  if (S % 256 == 0)
-    hipLaunchKernelGGL(attn_bwd_dkv_kernel<2>, dim3(S / 256, h, B), dim3(256), 0, st, (const bf16*)qkv,
-                       (const bf16*)d_o, lse, dscratch, (bf16*)dqkv, S, h, scale);
-  else
-    hipLaunchKernelGGL(attn_bwd_dkv_kernel<1>, dim3(S / 128, h, B), dim3(256), 0, st, (const bf16*)qkv,
-                       (const bf16*)d_o, lse, dscratch, (bf16*)dqkv, S, h, scale);
+  // one 32-key block per wavefront: two blocks (KT = 2) halve the Q / dO tile traffic but need
+  // more than 256 registers, which costs the second resident workgroup and AGPR copies
+  hipLaunchKernelGGL(attn_bwd_dkv_kernel<1>, dim3(S / 128 * h * B), dim3(256), 0, st, (const bf16*)qkv,
+                     (const bf16*)d_o, lse, dscratch, (bf16*)dqkv, S, h, B, scale);
   ALS_CHECK_LAUNCH();
   return ALS_OK;
 }
