@@ -23,10 +23,12 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 
 def flops_per_token(w):
-    """Algorithmic training FLOPs per token: 3 x [L (24 d^2 + 2 S d) + 2 d V] (causal attention
-    counted at half, backward = 2 x forward, no recompute credit)."""
-    L, d, S, V = w["L"], w["d"], w["S"], w["V"]
-    return 3.0 * (L * (24.0 * d * d + 2.0 * S * d) + 2.0 * d * V)
+    """Algorithmic training FLOPs per token: 3 x [L (8 d a + 4 d ff + 2 S a) + 2 d V], a = attention
+    width (= d unless the workload sets a head width); causal attention counted at half, backward
+    = 2 x forward, no recompute credit.  With a = d and ff = 4 d this is 3 [L (24 d^2 + 2 S d) + 2 d V]."""
+    L, d, S, V, ff = w["L"], w["d"], w["S"], w["V"], w["ff"]
+    a = w["h"] * w["dh"] if w.get("dh") else d
+    return 3.0 * (L * (8.0 * d * a + 4.0 * d * ff + 2.0 * S * a) + 2.0 * d * V)
 
 
 def cpu_baseline(w, seconds_hint=20.0):
