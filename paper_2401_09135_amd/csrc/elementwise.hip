@@ -542,6 +542,7 @@ int embed_bwd(const int32_t* tok, const int32_t* offset, const int32_t* pos, con
 // ------------------------------------------------------------------------------------------
 // RMSNorm: y = x * rsqrt(mean(x^2) + eps) * g ; one 64-lane wavefront per row.
 // ------------------------------------------------------------------------------------------
+#define RMS_MAXD4 4  // float4 slots per lane: d <= 1024
 template <typename OT>
 __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const float* __restrict__ x,
                                                           const float* __restrict__ g,
@@ -551,27 +552,36 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const float* __restric
   int lane = threadIdx.x & 63;
   int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= T) return;
+  const int d4 = d / 4;
   const float4* xr = reinterpret_cast<const float4*>(x + (int64_t)row * d);
   const float4* g4 = reinterpret_cast<const float4*>(g);
+  float4 v[RMS_MAXD4];  // the row is read once and stays in registers (d <= 1024)
   float ss = 0.0f;
-  for (int c = lane; c < d / 4; c += 64) {
-    float4 v = xr[c];
-    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+#pragma unroll
+  for (int s = 0; s < RMS_MAXD4; s++) {
+    int c = lane + 64 * s;
+    v[s] = c < d4 ? xr[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+    ss += v[s].x * v[s].x + v[s].y * v[s].y + v[s].z * v[s].z + v[s].w * v[s].w;
   }
   ss = wave_sum(ss);
   float r = 1.0f / sqrtf(ss / (float)d + eps);
   if (lane == 0) rstd[row] = r;
   OT* yr = y + (int64_t)row * d;
-  for (int c = lane; c < d / 4; c += 64) {
-    float4 v = xr[c], gg = g4[c];
-    float4 o = make_float4(v.x * r * gg.x, v.y * r * gg.y, v.z * r * gg.z, v.w * r * gg.w);
-    if (sizeof(OT) == 2) store_bf16x4(reinterpret_cast<bf16*>(yr) + 4 * c, o);
-    else reinterpret_cast<float4*>(yr)[c] = o;
+#pragma unroll
+  for (int s = 0; s < RMS_MAXD4; s++) {
+    int c = lane + 64 * s;
+    if (c < d4) {
+      float4 gg = g4[c];
+      float4 o = make_float4(v[s].x * r * gg.x, v[s].y * r * gg.y, v[s].z * r * gg.z, v[s].w * r * gg.w);
+      if (sizeof(OT) == 2) store_bf16x4(reinterpret_cast<bf16*>(yr) + 4 * c, o);
+      else reinterpret_cast<float4*>(yr)[c] = o;
+    }
   }
 }
 
 int rmsnorm_fwd(const float* x, const float* g, void* y, float* rstd, int T, int d, float eps,
                 int out_bf16, hipStream_t st) {
+  if (d > 256 * RMS_MAXD4 || d % 4) return set_error(ALS_ERR_INVALID, "rmsnorm_fwd: d unsupported");
   dim3 grid((T + 3) / 4), block(256);
   if (out_bf16)
     hipLaunchKernelGGL(rmsnorm_fwd_kernel<bf16>, grid, block, 0, st, x, g, (bf16*)y, rstd, T, d, eps);

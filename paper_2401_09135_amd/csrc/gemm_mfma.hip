@@ -266,15 +266,38 @@ __global__ __launch_bounds__(256, OCC) void gemm_mfma_kernel(MfmaArgs g) {
   // measured 8 % slower on the whole step.)
   TO* C = reinterpret_cast<TO*>(g.C);
   if (SPLIT) C += (int64_t)zsplit * g.split_stride;
-  __syncthreads();  // every wave is done with the operand tiles
   constexpr int PITCH = WN * 4 + 16;  // rows 4 banks apart: 16-byte accesses of 16 rows, or of two row halves, never collide
   static_assert(4 * 32 * PITCH <= TL::LDS_BYTES, "epilogue staging must fit the operand buffers");
   char* stg = smem + wave * (32 * PITCH);
   constexpr int CPL = sizeof(TO) == 2 ? 8 : 4;  // consecutive columns per lane
   constexpr int LPR = WN / CPL;                 // lanes per row
   constexpr int RPP = 64 / LPR;                 // rows per pass
+  constexpr int NPASS = 32 / RPP;
+  // The epilogue's global READS (residual rows, saved derivative) are issued together, ahead of
+  // the staging and the stores: loads and stores complete out of order with respect to each
+  // other, so a load issued after a store can only be waited for with "everything done", and a
+  // load per pass would expose one full memory latency per pass.  All of the sub-tile at once
+  // when that fits in 64 registers, else one 32-row block at a time.
+  constexpr bool HAS_AUX = EPI == EPI_RESID || EPI == EPI_DGELU;
+  constexpr bool AUX_ALL = TM * NPASS * 4 <= 64;
+  u32x4 aux[HAS_AUX ? TM : 1][HAS_AUX ? NPASS : 1];
+  auto load_aux = [&](int i) {
+#pragma unroll
+    for (int pass = 0; pass < NPASS; pass++) {
+      const int row = m0 + wm * WM + i * 32 + pass * RPP + lane / LPR;
+      const int col = n0 + wn * WN + (lane % LPR) * CPL;
+      if (EPI == EPI_RESID) aux[i][pass] = *reinterpret_cast<const u32x4*>(g.R + (int64_t)row * g.ldr + col);
+      else aux[i][pass] = *reinterpret_cast<const u32x4*>(g.U + (int64_t)row * g.ldc + col);
+    }
+  };
+  if (HAS_AUX && AUX_ALL) {
+#pragma unroll
+    for (int i = 0; i < TM; i++) load_aux(i);
+  }
+  __syncthreads();  // every wave is done with the operand tiles
 #pragma unroll
   for (int i = 0; i < TM; i++) {
+    if (HAS_AUX && !AUX_ALL) load_aux(i);
 #pragma unroll
     for (int j = 0; j < TN; j++)
 #pragma unroll
@@ -284,7 +307,7 @@ __global__ __launch_bounds__(256, OCC) void gemm_mfma_kernel(MfmaArgs g) {
       }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // wave-local staging: its own writes have landed
 #pragma unroll
-    for (int pass = 0; pass < 32 / RPP; pass++) {
+    for (int pass = 0; pass < NPASS; pass++) {
       const int rr = pass * RPP + lane / LPR;
       const int cc = (lane % LPR) * CPL;
       const int row = m0 + wm * WM + i * 32 + rr;
@@ -297,12 +320,12 @@ __global__ __launch_bounds__(256, OCC) void gemm_mfma_kernel(MfmaArgs g) {
         x[4 * q] = v[0]; x[4 * q + 1] = v[1]; x[4 * q + 2] = v[2]; x[4 * q + 3] = v[3];
       }
       if (EPI == EPI_RESID) {
-        f32x4 r = *reinterpret_cast<const f32x4*>(g.R + (int64_t)row * g.ldr + col);
+        f32x4 r = __builtin_bit_cast(f32x4, aux[HAS_AUX ? i : 0][HAS_AUX ? pass : 0]);
 #pragma unroll
         for (int e = 0; e < 4; e++) x[e] += r[e];
       }
       if (EPI == EPI_DGELU) {  // U holds gelu'(pre-activation), saved by the forward pass
-        bf16x8 u = *reinterpret_cast<const bf16x8*>(g.U + ci);
+        bf16x8 u = __builtin_bit_cast(bf16x8, aux[HAS_AUX ? i : 0][HAS_AUX ? pass : 0]);
 #pragma unroll
         for (int e = 0; e < CPL; e++) x[e] *= (float)u[e & 7];
       }
@@ -336,13 +359,18 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
                                                             float* __restrict__ C, int64_t n4,
                                                             int nsplit, int64_t stride4) {
   int64_t step = (int64_t)gridDim.x * blockDim.x;
+  const f32x4* p4 = reinterpret_cast<const f32x4*>(part);
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += step) {
-    float4 a = reinterpret_cast<const float4*>(part)[i];
-    for (int s = 1; s < nsplit; s++) {
-      float4 b = reinterpret_cast<const float4*>(part)[i + s * stride4];
-      a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    f32x4 a = p4[i];
+    for (int s0 = 1; s0 < nsplit; s0 += 8) {  // 8 partials in flight, added in split order
+      f32x4 b[8];
+#pragma unroll
+      for (int u = 0; u < 8; u++) b[u] = s0 + u < nsplit ? p4[i + (s0 + u) * stride4] : (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int u = 0; u < 8; u++)
+        if (s0 + u < nsplit) a += b[u];
     }
-    reinterpret_cast<float4*>(C)[i] = a;
+    reinterpret_cast<f32x4*>(C)[i] = a;
   }
 }
 
