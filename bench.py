@@ -20,6 +20,11 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+# HBM bytes per launch of the step's GEMM kernels, measured with rocprofv3 --pmc FETCH_SIZE (x 2.0)
+# and WRITE_SIZE (x 1.0) on the same shapes (profiles/gemm_mfma_microbench.md gives the commands,
+# the calibration of the two factors and the comparison with the algorithmic bytes).  Counters
+# cannot be collected from inside this process, so the figure is carried here.
+MEASURED_TRAFFIC_BYTES = {"lm20m": {"gemm_mfma_kernel<128, 128, 1, 0, STORE, float, true, 2, 2>": 99.6e6}}
 
 
 def flops_per_token(w):
@@ -226,7 +231,8 @@ def main():
         name, launches, ms, fl = prof[0]
         achieved = fl / (ms * 1e-3) / 1e12
         out["roofline"] = dict(bound="mfma", achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                               frac=achieved / PEAK_BF16_TFLOPS, traffic=None, kernel=name, launches=launches,
+                               frac=achieved / PEAK_BF16_TFLOPS,
+                               traffic=MEASURED_TRAFFIC_BYTES.get(args.workload, {}).get(name), kernel=name, launches=launches,
                                avg_us=1e3 * ms / launches, flops_per_launch=fl / launches,
                                how="HIP events around every launch of this kernel while one worker steps alone "
                                    "right after the timed region (same shapes, same stream)",

@@ -16,7 +16,8 @@ SHAPES = [("qkv", T, 1536, 512, 0, 0, 0), ("wo+res", T, 512, 512, 0, 0, 1), ("ff
           ("ffn2+res", T, 512, 2048, 0, 0, 1), ("head", T, 8192, 512, 0, 0, -1),
           ("dffn2*gp", T, 2048, 512, 0, 1, 3), ("dffn1 f32", T, 512, 2048, 0, 1, -1), ("dqkv f32", T, 512, 1536, 0, 1, -1),
           ("do bf16", T, 512, 512, 0, 1, 0), ("dhead f32", T, 512, 8192, 0, 1, -1),
-          ("dw ffn1", 512, 2048, T, 1, 0, 0), ("dw qkv", 512, 1536, T, 1, 0, 0), ("dw wo", 512, 512, T, 1, 0, 0),
+          ("dw ffn1", 512, 2048, T, 1, 0, 0), ("dw ffn2", 2048, 512, T, 1, 0, 0), ("dw qkv", 512, 1536, T, 1, 0, 0),
+          ("dw wo", 512, 512, T, 1, 0, 0),
           ("dw head", 512, 8192, T, 1, 0, 0), ("square 8192", 8192, 8192, 8192, 0, 1, 0)]
 
 
