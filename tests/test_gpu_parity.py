@@ -253,3 +253,44 @@ def test_comparison_outer_rules_match_oracle(name, N, rule):
     # the rule really changed the trajectory
     plain = run.run_async(w, theta0, _stream(w))
     assert _rel(plain["theta"], ref["theta"]) > (10 if w["dtype"] == "f32" else 3) * _rel(got["theta"], ref["theta"])
+
+
+@pytest.mark.parametrize("name", ["tiny", "wide_attn_f32", "mini_bf16"])
+@pytest.mark.parametrize("pattern", ["one_token", "two_tokens", "all_distinct_cycle", "out_of_range"])
+def test_embedding_gradient_token_patterns(name, pattern):
+    """The embedding gradient is built from a sorted position list cut into 32-position chunks:
+    one token filling every chunk, lists that end exactly on chunk borders, a ragged last chunk
+    (B*S = 72 in wide_attn_f32), many absent tokens, and ids the kernels clamp."""
+    w = I.workload(name)
+    B, S, V = w["B"], w["S"], w["V"]
+    n = B * (S + 1)
+    if pattern == "one_token":
+        tok = np.full(n, 3, np.int32)
+    elif pattern == "two_tokens":       # 32 x token 7, then token 1: the first list ends on a chunk border
+        tok = np.ones(n, np.int32)
+        tok[:min(32, n)] = 7
+    elif pattern == "all_distinct_cycle":
+        tok = (np.arange(n) % V).astype(np.int32)
+    else:
+        tok = (np.arange(n) % V).astype(np.int32)
+        tok[::5] = V + 11               # clamped to V - 1 by the library
+        tok[1::7] = -3                  # clamped to 0
+    tok = tok.reshape(B, S + 1)
+    ref_tok = np.clip(tok, 0, V - 1)
+    theta0 = I.theta0(lm.param_layout(w), w["seed"])
+    theta0 = theta0 + (np.random.default_rng(2).standard_normal(theta0.size) * 0.01).astype(np.float32)
+    ctx = A.Context(A.Config.from_workload(w), theta0, n_streams=1)
+    loss, g = ctx.worker_loss_grad(0, torch.from_numpy(tok).to("cuda:0"))
+    loss2, g2 = ctx.worker_loss_grad(0, torch.from_numpy(tok).to("cuda:0"))
+    ctx.close()
+    assert loss == loss2 and np.array_equal(g, g2)          # no atomics: bit-reproducible
+    rloss, rg = lm.loss_and_grad(theta0.copy(), ref_tok, w)
+    bf = w["dtype"] == "bf16"
+    assert abs(loss - rloss) / abs(rloss) < TOL[w["dtype"]]["loss"]
+    gv, rv = lm.views(g, w), lm.views(rg, w)
+    assert _rel(gv["E"], rv["E"]) < (1.5e-2 if bf else 1e-5)
+    assert _rel(gv["Ppos"], rv["Ppos"]) < (1.5e-2 if bf else 1e-5)
+    absent = sorted(set(range(V)) - set(ref_tok[:, :-1].reshape(-1).tolist()))
+    if absent:
+        assert not gv["E"][absent].any()                      # exact zeros for tokens that do not occur
+    _record(f"embed_patterns {name} {pattern}: E rel {_rel(gv['E'], rv['E']):.3e} Ppos rel {_rel(gv['Ppos'], rv['Ppos']):.3e}")
