@@ -52,6 +52,11 @@ WORKLOADS = {
     # the paper's 150M model at its own per-worker batch (128 sequences of 256): a bench workload
     "paper150m_b128": dict(_COMMON, L=12, d=896, h=16, dh=64, ff=3584, V=32000, S=256, B=128,
                            dtype="bf16", k=4, speeds=[1.0, 1.2, 1.6, 2.4], H=50, N=4, n_events=4),
+    # layer normalisation (gain, no bias) instead of RMS normalisation, fp32 and bf16
+    "tiny_ln": dict(_COMMON, L=2, d=64, h=2, ff=256, V=256, S=32, B=8, dtype="f32", k=4, norm="layer",
+                    speeds=[1.0, 1.5, 2.0, 3.0], H=5, N=4, n_events=8),
+    "mini_bf16_ln": dict(_COMMON, L=2, d=256, h=4, ff=1024, V=1024, S=128, B=4, dtype="bf16", norm="layer",
+                         k=4, speeds=[1.0, 1.2, 1.6, 2.4], H=10, N=4, n_events=4),
     "wide_attn_f32": dict(_COMMON, L=2, d=64, h=4, dh=32, ff=128, V=200, S=24, B=3, dtype="f32",
                           k=2, speeds=[1.0, 2.0], H=2, N=2, n_events=4),
     # the 150M-class architecture on one 1024-token sequence per step (d 896 = 7 x 128, 14 heads,

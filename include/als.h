@@ -48,6 +48,8 @@ extern "C" {
 
 #define ALS_DTYPE_F32 0  /* fp32 everywhere (debug / reference mode) */
 #define ALS_DTYPE_BF16 1 /* bf16 GEMM and attention operands, fp32 accumulate, master, optimiser */
+#define ALS_NORM_RMS 0
+#define ALS_NORM_LAYER 1
 
 #define ALS_MAX_WORKERS 64
 
@@ -68,7 +70,8 @@ typedef struct als_config {
   int32_t flags;           /* bit 0: disable the MFMA kernels (use the generic ones) */
   int32_t head_dim;        /* 0 = d/h; otherwise the attention width h*head_dim may differ from d
                               (the paper's 60M / 150M models: 16 heads of 64 on d = 896) */
-  int32_t reserved0;       /* keeps the doubles 8-byte aligned; must be 0 */
+  int32_t norm_kind;       /* ALS_NORM_RMS (0): y = x rsqrt(mean x^2 + eps) g ; ALS_NORM_LAYER (1): layer
+                              normalisation with a gain and no bias, y = (x - mean x) rsqrt(var x + eps) g */
   double adam_beta1, adam_beta2, adam_eps, weight_decay; /* AdamW (inner optimiser) */
   double outer_lr, outer_beta, dn_c;                     /* Alg. 3: epsilon, beta, c in [0,1/N] */
   double norm_eps;                                       /* RMSNorm epsilon */

@@ -75,6 +75,34 @@ def rmsnorm_bwd(dy, x, rstd, g):
     return dx, dg
 
 
+def layernorm_fwd(x, g, eps):
+    """Layer normalisation with a gain and no bias (the model has no biases anywhere):
+    y = (x - mean) / sqrt(var + eps) * g, var = mean((x - mean)^2)."""
+    xc = x - np.mean(x, axis=-1, keepdims=True)
+    rstd = 1.0 / np.sqrt(np.mean(xc * xc, axis=-1, keepdims=True) + x.dtype.type(eps))
+    return xc * rstd * g, rstd
+
+
+def layernorm_bwd(dy, x, rstd, g):
+    xhat = (x - np.mean(x, axis=-1, keepdims=True)) * rstd
+    dg = np.sum((dy * xhat).reshape(-1, x.shape[-1]), axis=0)
+    dxhat = dy * g
+    dx = rstd * (dxhat - np.mean(dxhat, axis=-1, keepdims=True)
+                 - xhat * np.mean(dxhat * xhat, axis=-1, keepdims=True))
+    return dx, dg
+
+
+def _norm(cfg):
+    """(forward, backward) of the configured normalisation: cfg["norm"] = "rms" (default) or
+    "layer"."""
+    kind = cfg.get("norm", "rms")
+    if kind == "rms":
+        return rmsnorm_fwd, rmsnorm_bwd
+    if kind == "layer":
+        return layernorm_fwd, layernorm_bwd
+    raise ValueError(f"unknown norm {kind!r}")
+
+
 _GELU_A = math.sqrt(2.0 / math.pi)
 _GELU_B = 0.044715
 
@@ -132,13 +160,14 @@ def forward(theta, tokens, cfg, keep=True):
     L, d, h, S = cfg["L"], cfg["d"], cfg["h"], cfg["S"]
     da = attention_width(cfg)
     eps = cfg["norm_eps"]
+    norm_fwd, _ = _norm(cfg)
     B = tokens.shape[0]
     assert tokens.shape[1] == S + 1
     inp, tgt = tokens[:, :S], tokens[:, 1:].reshape(-1)
     x = (p["E"][inp] + p["Ppos"][None, :, :]).reshape(B * S, d)
     layers = []
     for l in range(L):
-        a, rstd1 = rmsnorm_fwd(x, p[f"g1{l}"], eps)
+        a, rstd1 = norm_fwd(x, p[f"g1{l}"], eps)
         qkv = a @ p[f"Wqkv{l}"]
         q = _split_heads(qkv[:, :da], B, S, h)
         k = _split_heads(qkv[:, da:2 * da], B, S, h)
@@ -146,7 +175,7 @@ def forward(theta, tokens, cfg, keep=True):
         o4, prob = attention_fwd(q, k, v)
         o = _merge_heads(o4)
         xm = x + o @ p[f"Wo{l}"]
-        b, rstd2 = rmsnorm_fwd(xm, p[f"g2{l}"], eps)
+        b, rstd2 = norm_fwd(xm, p[f"g2{l}"], eps)
         u = b @ p[f"W1{l}"]
         gl = gelu_fwd(u)
         xn = xm + gl @ p[f"W2{l}"]
@@ -154,7 +183,7 @@ def forward(theta, tokens, cfg, keep=True):
             layers.append(dict(x=x, a=a, rstd1=rstd1, q=q, k=k, v=v, prob=prob, o=o, xm=xm,
                                b=b, rstd2=rstd2, u=u, gl=gl))
         x = xn
-    xf, rstdf = rmsnorm_fwd(x, p["gf"], eps)
+    xf, rstdf = norm_fwd(x, p["gf"], eps)
     logits = xf @ p["Wout"]
     mx = np.max(logits, axis=-1, keepdims=True)
     lse = mx[:, 0] + np.log(np.sum(np.exp(logits - mx), axis=-1))
@@ -179,7 +208,8 @@ def backward(theta, cache, cfg):
     dlogits = dlogits * theta.dtype.type(1.0 / T)
     g["Wout"][...] = cache["xf"].T @ dlogits
     dxf = dlogits @ p["Wout"].T
-    dx, dgf = rmsnorm_bwd(dxf, cache["x"], cache["rstdf"], p["gf"])
+    _, norm_bwd = _norm(cfg)
+    dx, dgf = norm_bwd(dxf, cache["x"], cache["rstdf"], p["gf"])
     g["gf"][...] = dgf
     for l in reversed(range(L)):
         c = cache["layers"][l]
@@ -188,7 +218,7 @@ def backward(theta, cache, cfg):
         du = dgl * gelu_grad(c["u"])
         g[f"W1{l}"][...] = c["b"].T @ du
         db = du @ p[f"W1{l}"].T
-        dxm_n, dg2 = rmsnorm_bwd(db, c["xm"], c["rstd2"], p[f"g2{l}"])
+        dxm_n, dg2 = norm_bwd(db, c["xm"], c["rstd2"], p[f"g2{l}"])
         g[f"g2{l}"][...] = dg2
         dxm = dx + dxm_n
         g[f"Wo{l}"][...] = c["o"].T @ dxm
@@ -197,7 +227,7 @@ def backward(theta, cache, cfg):
         dqkv = np.concatenate([_merge_heads(dq), _merge_heads(dk), _merge_heads(dv)], axis=1)
         g[f"Wqkv{l}"][...] = c["a"].T @ dqkv
         da = dqkv @ p[f"Wqkv{l}"].T
-        dx_n, dg1 = rmsnorm_bwd(da, c["x"], c["rstd1"], p[f"g1{l}"])
+        dx_n, dg1 = norm_bwd(da, c["x"], c["rstd1"], p[f"g1{l}"])
         g[f"g1{l}"][...] = dg1
         dx = dxm + dx_n
     dx3 = dx.reshape(B, S, d)

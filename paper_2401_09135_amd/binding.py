@@ -40,7 +40,7 @@ class Config(C.Structure):
                 ("d_ff", C.c_int32), ("vocab", C.c_int32), ("seq_len", C.c_int32),
                 ("batch", C.c_int32), ("dtype", C.c_int32), ("n_workers", C.c_int32),
                 ("dn_N", C.c_int32), ("max_local_steps", C.c_int32), ("flags", C.c_int32),
-                ("head_dim", C.c_int32), ("reserved0", C.c_int32),
+                ("head_dim", C.c_int32), ("norm_kind", C.c_int32),
                 ("adam_beta1", C.c_double), ("adam_beta2", C.c_double), ("adam_eps", C.c_double),
                 ("weight_decay", C.c_double), ("outer_lr", C.c_double), ("outer_beta", C.c_double),
                 ("dn_c", C.c_double), ("norm_eps", C.c_double)]
@@ -50,7 +50,7 @@ class Config(C.Structure):
         return cls(n_layers=w["L"], d_model=w["d"], n_heads=w["h"], d_ff=w["ff"], vocab=w["V"],
                    seq_len=w["S"], batch=w["B"], dtype=ALS_DTYPE_BF16 if w["dtype"] == "bf16" else ALS_DTYPE_F32,
                    n_workers=w["k"], dn_N=w["N"], max_local_steps=max_local_steps or w["H"], flags=flags,
-                   head_dim=int(w.get("dh", 0)), reserved0=0,
+                   head_dim=int(w.get("dh", 0)), norm_kind={"rms": 0, "layer": 1}[w.get("norm", "rms")],
                    adam_beta1=w["beta1"], adam_beta2=w["beta2"], adam_eps=w["adam_eps"],
                    weight_decay=w["wd"], outer_lr=w["outer_lr"], outer_beta=w["outer_beta"],
                    dn_c=w["dn_c"], norm_eps=w["norm_eps"])

@@ -80,14 +80,15 @@ int attention_bwd_mfma(const void* qkv, const void* o, const void* d_o, const fl
 // ---- elementwise / reductions ----------------------------------------------------------------
 int embed_fwd(const int32_t* tok, const float* E, const float* Ppos, float* x, int B, int S, int d,
               int V, hipStream_t st);
+// center = 0: RMSNorm ; 1: LayerNorm with gain and no bias
 int rmsnorm_fwd(const float* x, const float* g, void* y, float* rstd, int T, int d, float eps,
-                int out_bf16, hipStream_t st);
+                int out_bf16, int center, hipStream_t st);
 // dx_out = (dx_in ? dx_in : 0) + rmsnorm_backward(dy); optional low-precision copy of dx_out;
 // dg = sum over rows of dy * xhat (uses partial[nblk*d] scratch, nblk = rmsnorm_bwd_blocks()).
 int rmsnorm_bwd_blocks(int T);
 int rmsnorm_bwd(const float* dy, const float* x, const float* rstd, const float* g,
                 const float* dx_in, float* dx_out, void* dx_lp, int lp_bf16, float* dg,
-                float* partial, int T, int d, hipStream_t st);
+                float* partial, int T, int d, int center, hipStream_t st);
 int cross_entropy(const float* logits, const int32_t* tok, float* loss_row, void* dlogits,
                   int dl_bf16, int B, int S, int V, hipStream_t st);
 int mean_rows(const float* loss_row, float* out, int T, hipStream_t st);

@@ -129,11 +129,12 @@ int forward(als_ctx* c, Worker& w, const int32_t* tok, float* loss_out) {
   hipStream_t st = w.stream;
   int T = c->T, d = g.d_model, ff = g.d_ff, V = g.vocab, B = g.batch, S = g.seq_len, h = g.n_heads;
   const int dh = head_width(g), da = h * dh;
+  const int ln = g.norm_kind == ALS_NORM_LAYER;  // LayerNorm (gain, no bias) instead of RMSNorm
   bool mf = c->allow_mfma;
   float eps = (float)g.norm_eps;
   RUN(embed_fwd(tok, w.theta + L.E, w.theta + L.Ppos, w.x[0], B, S, d, V, st));
   for (int l = 0; l < g.n_layers; l++) {
-    RUN(rmsnorm_fwd(w.x[l], w.theta + L.g1[l], w.a[l], w.rstd1[l], T, d, eps, c->bf, st));
+    RUN(rmsnorm_fwd(w.x[l], w.theta + L.g1[l], w.a[l], w.rstd1[l], T, d, eps, c->bf, ln, st));
     RUN(gemm(desc(c, w.a[l], 0, d, wptr(c, w, L.Wqkv[l]), 0, 3 * da, T, 3 * da, d, w.qkv[l], 3 * da, true), mf, st));
     if (mf && attention_mfma_supported(S, dh, c->bf))
       RUN(attention_fwd_mfma(w.qkv[l], w.o[l], w.lse[l], B, S, h, dh, st));
@@ -142,7 +143,7 @@ int forward(als_ctx* c, Worker& w, const int32_t* tok, float* loss_out) {
     GemmDesc po = desc(c, w.o[l], 0, da, wptr(c, w, L.Wo[l]), 0, d, T, d, da, w.xm[l], d, false);
     po.epi = EPI_RESID; po.R = w.x[l]; po.ldr = d;
     RUN(gemm(po, mf, st));
-    RUN(rmsnorm_fwd(w.xm[l], w.theta + L.g2[l], w.b[l], w.rstd2[l], T, d, eps, c->bf, st));
+    RUN(rmsnorm_fwd(w.xm[l], w.theta + L.g2[l], w.b[l], w.rstd2[l], T, d, eps, c->bf, ln, st));
     GemmDesc f1 = desc(c, w.b[l], 0, d, wptr(c, w, L.W1[l]), 0, ff, T, ff, d, w.u[l], ff, true);
     f1.epi = EPI_GELU; f1.C2 = w.gl[l];
     RUN(gemm(f1, mf, st));
@@ -150,7 +151,7 @@ int forward(als_ctx* c, Worker& w, const int32_t* tok, float* loss_out) {
     f2.epi = EPI_RESID; f2.R = w.xm[l]; f2.ldr = d;
     RUN(gemm(f2, mf, st));
   }
-  RUN(rmsnorm_fwd(w.x[g.n_layers], w.theta + L.gf, w.xf, w.rstdf, T, d, eps, c->bf, st));
+  RUN(rmsnorm_fwd(w.x[g.n_layers], w.theta + L.gf, w.xf, w.rstdf, T, d, eps, c->bf, ln, st));
   RUN(gemm(desc(c, w.xf, 0, d, wptr(c, w, L.Wout), 0, V, T, V, d, w.logits, V, false), mf, st));
   RUN(cross_entropy(w.logits, tok, w.loss_row, w.dlogits, c->bf, B, S, V, st));
   RUN(mean_rows(w.loss_row, loss_out, T, st));
@@ -163,13 +164,14 @@ int backward(als_ctx* c, Worker& w, const int32_t* tok, int slot) {
   hipStream_t st = w.stream;
   int T = c->T, d = g.d_model, ff = g.d_ff, V = g.vocab, B = g.batch, S = g.seq_len, h = g.n_heads;
   const int dh = head_width(g), da = h * dh;
+  const int ln = g.norm_kind == ALS_NORM_LAYER;  // LayerNorm (gain, no bias) instead of RMSNorm
   bool mf = c->allow_mfma;
   int nl = g.n_layers;
   // output matrix and final norm
   RUN(gemm(desc_dw(c, w, w.xf, d, w.dlogits, V, d, V, T, w.grad + L.Wout), mf, st));
   RUN(gemm(desc(c, w.dlogits, 0, V, wptr(c, w, L.Wout), 1, V, T, d, V, w.dtmp, d, false), mf, st));
   RUN(rmsnorm_bwd(w.dtmp, w.x[nl], w.rstdf, w.theta + L.gf, nullptr, w.dxa, w.dx_lp, c->bf,
-                  w.grad + L.gf, w.partial, T, d, st));
+                  w.grad + L.gf, w.partial, T, d, ln, st));
   for (int l = nl - 1; l >= 0; l--) {
     // feed-forward block: x_next = xm + gelu(b W1) W2
     RUN(gemm(desc_dw(c, w, w.gl[l], ff, w.dx_lp, d, ff, d, T, w.grad + L.W2[l]), mf, st));
@@ -179,7 +181,7 @@ int backward(als_ctx* c, Worker& w, const int32_t* tok, int slot) {
     RUN(gemm(desc_dw(c, w, w.b[l], d, w.dff, ff, d, ff, T, w.grad + L.W1[l]), mf, st));
     RUN(gemm(desc(c, w.dff, 0, ff, wptr(c, w, L.W1[l]), 1, ff, T, d, ff, w.dtmp, d, false), mf, st));
     RUN(rmsnorm_bwd(w.dtmp, w.xm[l], w.rstd2[l], w.theta + L.g2[l], w.dxa, w.dxb, w.dx_lp, c->bf,
-                    w.grad + L.g2[l], w.partial, T, d, st));
+                    w.grad + L.g2[l], w.partial, T, d, ln, st));
     // attention block: xm = x + attn(a Wqkv) Wo
     RUN(gemm(desc_dw(c, w, w.o[l], da, w.dx_lp, d, da, d, T, w.grad + L.Wo[l]), mf, st));
     RUN(gemm(desc(c, w.dx_lp, 0, d, wptr(c, w, L.Wo[l]), 1, d, T, da, d, w.d_o, da, true), mf, st));
@@ -190,7 +192,7 @@ int backward(als_ctx* c, Worker& w, const int32_t* tok, int slot) {
     RUN(gemm(desc_dw(c, w, w.a[l], d, w.dqkv, 3 * da, d, 3 * da, T, w.grad + L.Wqkv[l]), mf, st));
     RUN(gemm(desc(c, w.dqkv, 0, 3 * da, wptr(c, w, L.Wqkv[l]), 1, 3 * da, T, d, 3 * da, w.dtmp, d, false), mf, st));
     RUN(rmsnorm_bwd(w.dtmp, w.x[l], w.rstd1[l], w.theta + L.g1[l], w.dxb, w.dxa, w.dx_lp, c->bf,
-                    w.grad + L.g1[l], w.partial, T, d, st));
+                    w.grad + L.g1[l], w.partial, T, d, ln, st));
   }
   // w.dtmp (T x d floats) is free again here: scratch for the embedding gradient's chunk partials
   RUN(embed_bwd(tok, w.sort_offset + (int64_t)slot * (V + 1), w.sort_pos + (int64_t)slot * T, w.dxa,

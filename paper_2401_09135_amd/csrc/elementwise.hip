@@ -540,10 +540,13 @@ int embed_bwd(const int32_t* tok, const int32_t* offset, const int32_t* pos, con
 }
 
 // ------------------------------------------------------------------------------------------
-// RMSNorm: y = x * rsqrt(mean(x^2) + eps) * g ; one 64-lane wavefront per row.
+// Normalisation over the feature dimension, one 64-lane wavefront per row:
+//   RMSNorm   (CENTER = false): y = x * rsqrt(mean(x^2) + eps) * g
+//   LayerNorm (CENTER = true):  y = (x - mean(x)) * rsqrt(mean((x - mean(x))^2) + eps) * g   (no bias)
+// rstd[row] is saved for the backward pass (which recomputes the mean from the row it reads).
 // ------------------------------------------------------------------------------------------
 #define RMS_MAXD4 4  // float4 slots per lane: d <= 1024
-template <typename OT>
+template <typename OT, bool CENTER>
 __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const float* __restrict__ x,
                                                           const float* __restrict__ g,
                                                           OT* __restrict__ y,
@@ -556,11 +559,19 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const float* __restric
   const float4* xr = reinterpret_cast<const float4*>(x + (int64_t)row * d);
   const float4* g4 = reinterpret_cast<const float4*>(g);
   float4 v[RMS_MAXD4];  // the row is read once and stays in registers (d <= 1024)
-  float ss = 0.0f;
+  float sum = 0.0f;
 #pragma unroll
   for (int s = 0; s < RMS_MAXD4; s++) {
     int c = lane + 64 * s;
     v[s] = c < d4 ? xr[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+    sum += (v[s].x + v[s].y) + (v[s].z + v[s].w);
+  }
+  const float mean = CENTER ? wave_sum(sum) / (float)d : 0.0f;
+  float ss = 0.0f;
+#pragma unroll
+  for (int s = 0; s < RMS_MAXD4; s++) {
+    int c = lane + 64 * s;
+    if (CENTER && c < d4) { v[s].x -= mean; v[s].y -= mean; v[s].z -= mean; v[s].w -= mean; }
     ss += v[s].x * v[s].x + v[s].y * v[s].y + v[s].z * v[s].z + v[s].w * v[s].w;
   }
   ss = wave_sum(ss);
@@ -580,23 +591,27 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const float* __restric
 }
 
 int rmsnorm_fwd(const float* x, const float* g, void* y, float* rstd, int T, int d, float eps,
-                int out_bf16, hipStream_t st) {
+                int out_bf16, int center, hipStream_t st) {
   if (d > 256 * RMS_MAXD4 || d % 4) return set_error(ALS_ERR_INVALID, "rmsnorm_fwd: d unsupported");
   dim3 grid((T + 3) / 4), block(256);
-  if (out_bf16)
-    hipLaunchKernelGGL(rmsnorm_fwd_kernel<bf16>, grid, block, 0, st, x, g, (bf16*)y, rstd, T, d, eps);
-  else
-    hipLaunchKernelGGL(rmsnorm_fwd_kernel<float>, grid, block, 0, st, x, g, (float*)y, rstd, T, d, eps);
+  if (out_bf16) {
+    if (center) hipLaunchKernelGGL((rmsnorm_fwd_kernel<bf16, true>), grid, block, 0, st, x, g, (bf16*)y, rstd, T, d, eps);
+    else hipLaunchKernelGGL((rmsnorm_fwd_kernel<bf16, false>), grid, block, 0, st, x, g, (bf16*)y, rstd, T, d, eps);
+  } else {
+    if (center) hipLaunchKernelGGL((rmsnorm_fwd_kernel<float, true>), grid, block, 0, st, x, g, (float*)y, rstd, T, d, eps);
+    else hipLaunchKernelGGL((rmsnorm_fwd_kernel<float, false>), grid, block, 0, st, x, g, (float*)y, rstd, T, d, eps);
+  }
   ALS_CHECK_LAUNCH();
   return ALS_OK;
 }
 
-// Backward: xhat = x rstd ; dxhat = dy g ; dx = rstd (dxhat - xhat mean(dxhat xhat)) ;
+// Backward: xhat = x rstd (RMSNorm) or (x - mean x) rstd (LayerNorm) ; dxhat = dy g ;
+// dx = rstd (dxhat - xhat mean(dxhat xhat))  [LayerNorm: also - mean(dxhat)] ;
 // dg = sum_rows dy xhat.  Each block walks rows with a fixed stride and leaves one partial dg
 // row; a second kernel adds the partials in a fixed order.
 #define RMS_BWD_MAXD4 4  // per-lane float4 slots: supports d <= 1024
 // One wavefront per row, each row read once into registers; a wave keeps two rows in flight.
-template <typename LT>
+template <typename LT, bool CENTER>
 __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(
     const float* __restrict__ dy, const float* __restrict__ x, const float* __restrict__ rstd,
     const float* __restrict__ g, const float* dx_in, float* dx_out, LT* __restrict__ dx_lp,
@@ -615,7 +630,7 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(
   const int stride = gridDim.x * 4;
   for (int row0 = blockIdx.x * 4 + w; row0 < T; row0 += 2 * stride) {
     f32x4 xv[2][RMS_BWD_MAXD4], dv[2][RMS_BWD_MAXD4], av[2][RMS_BWD_MAXD4];
-    float r[2], dot[2];
+    float r[2], dot[2], m1[2];
     bool ok[2];
 #pragma unroll
     for (int u = 0; u < 2; u++) {
@@ -634,14 +649,26 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(
     }
 #pragma unroll
     for (int u = 0; u < 2; u++) {
-      float acc = 0.0f;
+      if (CENTER) {  // the row's mean, recomputed from the row in registers
+        float sx = 0.0f;
+#pragma unroll
+        for (int s = 0; s < RMS_BWD_MAXD4; s++) sx += (xv[u][s][0] + xv[u][s][1]) + (xv[u][s][2] + xv[u][s][3]);
+        const float mean = wave_sum(sx) * inv_d;
+#pragma unroll
+        for (int s = 0; s < RMS_BWD_MAXD4; s++)
+          if (lane + 64 * s < d4) xv[u][s] -= mean;
+      }
+      float acc = 0.0f, acc1 = 0.0f;
 #pragma unroll
       for (int s = 0; s < RMS_BWD_MAXD4; s++) {
         xv[u][s] *= r[u];  // xhat
-        f32x4 t = dv[u][s] * gg[s] * xv[u][s];
+        f32x4 dh = dv[u][s] * gg[s];
+        f32x4 t = dh * xv[u][s];
         acc += (t[0] + t[1]) + (t[2] + t[3]);
+        if (CENTER) acc1 += (dh[0] + dh[1]) + (dh[2] + dh[3]);
       }
       dot[u] = wave_sum(acc) * inv_d;
+      m1[u] = CENTER ? wave_sum(acc1) * inv_d : 0.0f;
     }
 #pragma unroll
     for (int u = 0; u < 2; u++) {
@@ -652,7 +679,7 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(
         int c = lane + 64 * s;
         if (c < d4) {
           dg[s] += dv[u][s] * xv[u][s];
-          f32x4 o = r[u] * (dv[u][s] * gg[s] - xv[u][s] * dot[u]) + av[u][s];
+          f32x4 o = r[u] * (dv[u][s] * gg[s] - m1[u] - xv[u][s] * dot[u]) + av[u][s];
           int64_t oi = (int64_t)row * d4 + c;
           reinterpret_cast<f32x4*>(dx_out)[oi] = o;
           if (dx_lp) {
@@ -710,16 +737,19 @@ int rmsnorm_bwd_blocks(int T) {
 
 int rmsnorm_bwd(const float* dy, const float* x, const float* rstd, const float* g,
                 const float* dx_in, float* dx_out, void* dx_lp, int lp_bf16, float* dg,
-                float* partial, int T, int d, hipStream_t st) {
+                float* partial, int T, int d, int center, hipStream_t st) {
   if (d > 256 * RMS_BWD_MAXD4 || d % 4) return set_error(ALS_ERR_INVALID, "rmsnorm_bwd: d unsupported");
   int nblk = rmsnorm_bwd_blocks(T);
   size_t sm = (size_t)4 * d * sizeof(float);
-  if (lp_bf16)
-    hipLaunchKernelGGL(rmsnorm_bwd_kernel<bf16>, dim3(nblk), dim3(256), sm, st, dy, x, rstd, g, dx_in,
-                       dx_out, (bf16*)dx_lp, partial, T, d);
-  else
-    hipLaunchKernelGGL(rmsnorm_bwd_kernel<float>, dim3(nblk), dim3(256), sm, st, dy, x, rstd, g, dx_in,
-                       dx_out, (float*)dx_lp, partial, T, d);
+#define ALS_NORM_BWD(LT, CEN)                                                                                   \
+  hipLaunchKernelGGL((rmsnorm_bwd_kernel<LT, CEN>), dim3(nblk), dim3(256), sm, st, dy, x, rstd, g, dx_in, dx_out, \
+                     (LT*)dx_lp, partial, T, d)
+  if (lp_bf16) {
+    if (center) ALS_NORM_BWD(bf16, true); else ALS_NORM_BWD(bf16, false);
+  } else {
+    if (center) ALS_NORM_BWD(float, true); else ALS_NORM_BWD(float, false);
+  }
+#undef ALS_NORM_BWD
   ALS_CHECK_LAUNCH();
   hipLaunchKernelGGL(sum_partials_kernel, dim3((d + 31) / 32), dim3(1024), 0, st, partial, dg, nblk, d);
   ALS_CHECK_LAUNCH();

@@ -28,7 +28,8 @@ int validate_config(const als_config* c) {
   if (c->d_model < 64 || c->d_model % 64 || c->d_model > 1024)
     return set_error(ALS_ERR_INVALID, "d_model must be a multiple of 64 in 64..1024");
   if (c->n_heads < 1) return set_error(ALS_ERR_INVALID, "n_heads must be >= 1");
-  if (c->head_dim < 0 || c->reserved0 != 0) return set_error(ALS_ERR_INVALID, "head_dim must be >= 0 and reserved0 zero");
+  if (c->head_dim < 0) return set_error(ALS_ERR_INVALID, "head_dim must be >= 0");
+  if (c->norm_kind != ALS_NORM_RMS && c->norm_kind != ALS_NORM_LAYER) return set_error(ALS_ERR_INVALID, "unknown norm_kind");
   if (c->head_dim == 0 && c->d_model % c->n_heads) return set_error(ALS_ERR_INVALID, "d_model must be divisible by n_heads");
   int dh = head_width(*c);
   if (dh != 32 && dh != 64) return set_error(ALS_ERR_INVALID, "head width must be 32 or 64");

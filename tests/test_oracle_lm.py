@@ -13,7 +13,9 @@ CFG = dict(L=2, d=16, h=2, ff=40, V=23, S=6, norm_eps=1e-5)
 # attention width h * dh = 24 on a hidden size of 16 (the paper's larger models have 16 heads of
 # 64 on 896)
 CFG_WIDE = dict(L=2, d=16, h=3, dh=8, ff=40, V=23, S=6, norm_eps=1e-5)
-BOTH = pytest.mark.parametrize("CFG", [CFG, CFG_WIDE], ids=["square", "wide"])
+# layer normalisation (gain only) instead of RMS normalisation
+CFG_LN = dict(CFG, norm="layer")
+BOTH = pytest.mark.parametrize("CFG", [CFG, CFG_WIDE, CFG_LN], ids=["square", "wide", "layernorm"])
 
 
 def _theta(cfg, seed=0, sigma=0.3, dtype=np.float64):
@@ -101,15 +103,19 @@ def _torch_loss(theta_t, tok, cfg):
     tok = torch.as_tensor(tok, dtype=torch.long)
     B = tok.shape[0]
     x = F.embedding(tok[:, :S], E) + Ppos
+    if cfg.get("norm", "rms") == "layer":
+        norm = lambda t, g: F.layer_norm(t, (d,), g, None, cfg["norm_eps"])
+    else:
+        norm = lambda t, g: F.rms_norm(t, (d,), g, cfg["norm_eps"])
     for (Wqkv, Wo, W1, W2), (g1, g2) in zip(mats, gains):
-        a = F.rms_norm(x, (d,), g1, cfg["norm_eps"])
+        a = norm(x, g1)
         q, k, v = (a @ Wqkv).split(h * dh, dim=-1)
         q, k, v = (z.view(B, S, h, dh).transpose(1, 2) for z in (q, k, v))
         o = F.scaled_dot_product_attention(q, k, v, is_causal=True)
         x = x + o.transpose(1, 2).reshape(B, S, h * dh) @ Wo
-        b = F.rms_norm(x, (d,), g2, cfg["norm_eps"])
+        b = norm(x, g2)
         x = x + F.gelu(b @ W1, approximate="tanh") @ W2
-    logits = F.rms_norm(x, (d,), gf, cfg["norm_eps"]) @ Wout
+    logits = norm(x, gf) @ Wout
     return F.cross_entropy(logits.view(B * S, V), tok[:, 1:].reshape(-1))
 
 
@@ -175,3 +181,20 @@ def test_pieces_against_library():
     g = rng.standard_normal(8)
     y, _ = lm.rmsnorm_fwd(x, g, 1e-5)
     np.testing.assert_allclose(y, F.rms_norm(torch.tensor(x), (8,), torch.tensor(g), 1e-5).numpy(), atol=1e-14)
+    # layer normalisation (gain, no bias): forward against the library, backward against its
+    # autograd, and two closed forms of its input gradient: it sums to zero over a row, and along
+    # the centred row it is eps rstd^2 <dy g, xhat> (zero but for eps: y ignores the row's scale)
+    x = rng.standard_normal((5, 8)) + 0.7
+    y, rstd = lm.layernorm_fwd(x, g, 1e-5)
+    xt = torch.tensor(x, requires_grad=True)
+    gt = torch.tensor(g, requires_grad=True)
+    yt = F.layer_norm(xt, (8,), gt, None, 1e-5)
+    np.testing.assert_allclose(y, yt.detach().numpy(), atol=1e-14)
+    dy = rng.standard_normal((5, 8))
+    yt.backward(torch.tensor(dy))
+    dx, dg = lm.layernorm_bwd(dy, x, rstd, g)
+    np.testing.assert_allclose(dx, xt.grad.numpy(), atol=1e-13)
+    np.testing.assert_allclose(dg, gt.grad.numpy(), atol=1e-13)
+    np.testing.assert_allclose(dx.sum(axis=1), 0.0, atol=1e-13)
+    xc = x - x.mean(axis=1, keepdims=True)
+    np.testing.assert_allclose((dx * xc).sum(axis=1), 1e-5 * rstd[:, 0] ** 2 * (dy * g * xc * rstd).sum(axis=1), atol=1e-14)
