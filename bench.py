@@ -36,6 +36,39 @@ def flops_per_token(w):
     return 3.0 * (L * (8.0 * d * a + 4.0 * d * ff + 2.0 * S * a) + 2.0 * d * V)
 
 
+def _host_threads():
+    """(threads the BLAS behind numpy uses, its name)."""
+    try:
+        from threadpoolctl import threadpool_info
+        info = [p for p in threadpool_info() if p.get("user_api") == "blas"] or threadpool_info()
+        return max([p.get("num_threads", 1) for p in info] or [1]), "/".join(
+            sorted({f"{p.get('internal_api', '?')} {p.get('version', '')}".strip() for p in info})) or "unknown"
+    except Exception:
+        return os.cpu_count() or 1, "unknown"
+
+
+def cpu_baseline_outer(mb):
+    """The oracle's Delayed Nesterov event (pseudo-gradient + Alg. 3, numpy fp32) on the same
+    150M-element vectors: two non-boundary events timed, 24 algorithmic bytes per parameter."""
+    import numpy as np
+    import als_inputs as I
+    from oracle.optim import DelayedNesterov, pseudo_gradient
+    P = mb["P"]
+    rng = np.random.default_rng(mb["seed"])
+    theta = (rng.standard_normal(P, dtype=np.float32) * np.float32(mb["sigma"]))
+    start = (rng.standard_normal(P, dtype=np.float32) * np.float32(mb["sigma"]))
+    work = start + rng.standard_normal(P, dtype=np.float32) * np.float32(mb["drift_sigma"])
+    server = DelayedNesterov(theta, mb["outer_lr"], mb["outer_beta"], 4, 0.0)
+    t0 = time.perf_counter()
+    n = 2
+    for _ in range(n):
+        server.event(pseudo_gradient(start, work))
+    dt = (time.perf_counter() - t0) / n
+    return dict(value=P * 24 / dt / 1e9, unit="GB/s", cores=1, kind="oracle",
+                sample=f"{n} non-boundary Delayed-Nesterov events (N=4, c=0) on {P} fp32 parameters, numpy "
+                       f"elementwise arithmetic (single-threaded), {dt:.2f} s per event on {os.cpu_count()} host cpus")
+
+
 def cpu_baseline(w, seconds_hint=20.0):
     """The oracle as it stands, timed on the host: one local step (forward, backward, AdamW) of
     worker 0 on a slice of its batch, sized to take roughly 10-30 s."""
@@ -43,11 +76,7 @@ def cpu_baseline(w, seconds_hint=20.0):
     import als_inputs as I
     from oracle import lm
     from oracle.optim import AdamW
-    try:
-        from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:
-        threads = os.cpu_count() or 1
+    threads, blas = _host_threads()
     nb = max(1, w["B"] // 8)
     toks = I.TokenStream(w["seed"], 0, w["B"], w["S"], w["V"]).take(1)[0]
     while True:
@@ -63,7 +92,8 @@ def cpu_baseline(w, seconds_hint=20.0):
         nb = min(w["B"], nb * 4)      # grow the sample until it is worth about 10-30 s
     return dict(value=nb * w["S"] / dt, unit="tokens/s", cores=int(threads), kind="oracle",
                 sample=f"1 local step (forward+backward+AdamW, numpy fp32) of worker 0 on {nb} of its "
-                       f"{w['B']} sequences of {w['S']} tokens; {dt:.1f} s on {os.cpu_count()} host cpus")
+                       f"{w['B']} sequences of {w['S']} tokens; {dt:.1f} s on {os.cpu_count()} host cpus, "
+                       f"BLAS {blas} with {threads} threads")
 
 
 def outer_microbench(args):
@@ -124,8 +154,10 @@ def outer_microbench(args):
                data="synthetic", config=dict(workload=f"outer_microbench: {P} fp32 parameters, 16 replicas resident, "
                                                       "value = one non-boundary Delayed-Nesterov event (N=4, c=0)", results=res),
                roofline=dict(bound="hbm", achieved=res[key]["GBps"], peak=PEAK_HBM_GBS, unit="GB/s",
-                             frac=res[key]["GBps"] / PEAK_HBM_GBS, traffic=None, kernel="dn_group_kernel<4>"),
-               cpu_baseline=None)
+                             frac=res[key]["GBps"] / PEAK_HBM_GBS,
+                             # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 of this launch (profiles/outer_microbench_dn_adamw.md)
+                             traffic=(2343894 + 1171876) * 1024.0, kernel="dn_group_kernel<4>"),
+               cpu_baseline=None if args.no_cpu_baseline else cpu_baseline_outer(mb))
     print(json.dumps(out))
 
 
