@@ -194,7 +194,10 @@ def _stream_handle(stream) -> int:
 class Context:
     """Owns the arena (a torch uint8 tensor) and the worker streams; wraps als_ctx."""
 
-    def __init__(self, cfg: Config, theta0: np.ndarray, n_streams: int | None = None, device="cuda:0"):
+    def __init__(self, cfg: Config, theta0: np.ndarray, n_streams: int | None = None, device="cuda:0",
+                 streams=None):
+        """streams: optional list of torch streams to run the workers on (worker i uses stream
+        i mod len(streams)); by default one new stream per worker."""
         import torch
         self.torch = torch
         self.cfg = cfg
@@ -209,8 +212,11 @@ class Context:
         torch.cuda.set_device(self.device)
         self.arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
         base = (self.arena.data_ptr() + 255) // 256 * 256
-        n_streams = cfg.n_workers if n_streams is None else n_streams
-        self.streams = [torch.cuda.Stream(device=self.device) for _ in range(n_streams)]
+        if streams is not None:
+            self.streams, n_streams = list(streams), len(streams)
+        else:
+            n_streams = cfg.n_workers if n_streams is None else n_streams
+            self.streams = [torch.cuda.Stream(device=self.device) for _ in range(n_streams)]
         handles = (_P * n_streams)(*[_stream_handle(s) for s in self.streams])
         torch.cuda.synchronize()
         self._ctx = _P()

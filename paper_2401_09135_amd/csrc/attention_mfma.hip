@@ -239,34 +239,14 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16* __restrict
   if (hf == 0) lse[((int64_t)b * h + hd) * S + q] = (m_run * scale_log2 + log2f(l)) * LN2;
 }
 
-// D[b,h,q] = sum_c dO[q,c] O[q,c] : 8 lanes per (token, head)
-__global__ __launch_bounds__(256) void attn_bwd_rowdot_kernel(const bf16* __restrict__ o, const bf16* __restrict__ d_o,
-                                                              float* __restrict__ D, int S, int h, int64_t n_pairs) {
-  int64_t pair = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 3;
-  int sub = threadIdx.x & 7;
-  float acc = 0.0f;
-  if (pair < n_pairs) {
-    bf16x8 a = *reinterpret_cast<const bf16x8*>(o + pair * DH + sub * 8);
-    bf16x8 g = *reinterpret_cast<const bf16x8*>(d_o + pair * DH + sub * 8);
-#pragma unroll
-    for (int e = 0; e < 8; e++) acc += (float)a[e] * (float)g[e];
-  }
-  acc += __shfl_xor(acc, 1, 64);
-  acc += __shfl_xor(acc, 2, 64);
-  acc += __shfl_xor(acc, 4, 64);
-  if (pair < n_pairs && sub == 0) {
-    int64_t t = pair / h;
-    int hd = (int)(pair % h);
-    D[((t / S) * h + hd) * S + (t % S)] = acc;
-  }
-}
-
 // ------------------------------------------------------------------------------------------
-// backward, dQ: one workgroup per (128 queries, head, sample).  Per 64-key tile:
+// backward, dQ (and the row dots D = rowsum(dO * O), which it leaves for the dK/dV pass): one
+// workgroup per (128 queries, head, sample).  Per 64-key tile:
 //   S^T = K Q^T ; dP^T = V dO^T ; dS^T = P^T (dP^T - D) ; dQ^T += K^T dS^T
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ d_o,
-                                                          const float* __restrict__ lse, const float* __restrict__ D,
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ o,
+                                                          const bf16* __restrict__ d_o,
+                                                          const float* __restrict__ lse, float* __restrict__ D,
                                                           bf16* __restrict__ dqkv, int S, int h, int B, float scale) {
   __shared__ __attribute__((aligned(16))) char smem[4 * TILE_BYTES];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, hf = lane >> 5;
@@ -286,7 +266,17 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16* __restr
     gf[kk] = *reinterpret_cast<const bf16x8*>(dorow + kk * 16 + hf * 8);
   }
   const float lse2 = lse[((int64_t)b * h + hd) * S + q] * LOG2E;
-  const float Dq = D[((int64_t)b * h + hd) * S + q];
+  // D[q] = sum_c dO[q,c] O[q,c]: each lane holds half of its query's row; kept for the dK/dV pass
+  float Dq = 0.0f;
+  const bf16* orow = o + ((int64_t)b * S + q) * d + hd * DH;
+#pragma unroll
+  for (int kk = 0; kk < 4; kk++) {
+    bf16x8 of = *reinterpret_cast<const bf16x8*>(orow + kk * 16 + hf * 8);
+#pragma unroll
+    for (int e = 0; e < 8; e++) Dq += (float)of[e] * (float)gf[kk][e];
+  }
+  Dq += __shfl_xor(Dq, 32, 64);
+  if (hf == 0) D[((int64_t)b * h + hd) * S + q] = Dq;
 
   f32x16 dq[2] = {zero16(), zero16()};
   const int n_tiles = (q0 + 128) / 64;
@@ -528,12 +518,8 @@ int attention_bwd_mfma(const void* qkv, const void* o, const void* d_o, const fl
                        void* dqkv, int B, int S, int h, int dh, hipStream_t st) {
   if (!attention_mfma_supported(S, dh, 1) || B < 1 || h < 1) return set_error(ALS_ERR_INVALID, "attention_bwd_mfma: unsupported shape");
   float scale = 1.0f / sqrtf((float)dh);
-  int64_t n_pairs = (int64_t)B * S * h;
-  hipLaunchKernelGGL(attn_bwd_rowdot_kernel, dim3((unsigned)((n_pairs * 8 + 255) / 256)), dim3(256), 0, st,
-                     (const bf16*)o, (const bf16*)d_o, dscratch, S, h, n_pairs);
-  ALS_CHECK_LAUNCH();
-  hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(S / 128 * h * B), dim3(256), 0, st, (const bf16*)qkv, (const bf16*)d_o,
-                     lse, dscratch, (bf16*)dqkv, S, h, B, scale);
+  hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(S / 128 * h * B), dim3(256), 0, st, (const bf16*)qkv, (const bf16*)o,
+                     (const bf16*)d_o, lse, dscratch, (bf16*)dqkv, S, h, B, scale);
   ALS_CHECK_LAUNCH();
   // one 32-key block per wavefront: two blocks (KT = 2) halve the Q / dO tile traffic but need
   // more than 256 registers, which costs the second resident workgroup and AGPR copies

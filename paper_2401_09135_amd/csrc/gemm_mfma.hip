@@ -1,15 +1,17 @@
 // bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate) for the
 // worker step's projections: C[M,N] = sum_k A(m,k) B(k,n).
 //
-// One workgroup of 4 wavefronts (2 x 2) owns a BM x BN tile of C and walks K in slices of 64,
-// double-buffered through LDS; each wavefront owns a (BM/2) x (BN/2) sub-tile made of 32 x 32
-// MFMA blocks.  Operands may be stored with the contraction index contiguous (read from LDS
-// with 16-byte loads, rows padded by 16 bytes so that 8 neighbouring rows hit different banks)
-// or with the contraction index strided (read with the LDS transpose load ds_read_b64_tr_b16,
-// rows padded by 64 bytes), so forward (x W), input-gradient (dY W^T) and weight-gradient
-// (X^T dY) products all read the tensors as they lie in memory, without transposed copies.
-// Weight-gradient products have small M x N and very long K: they are split along K over
-// grid.z into fp32 partials that a second kernel adds in a fixed order.
+// One workgroup of 4 wavefronts (2 x 2) owns a BM x BN tile of C and walks K in slices of 64
+// staged through LDS (one buffer with 2-3 workgroups per CU, or two buffers); each wavefront
+// owns a (BM/2) x (BN/2) sub-tile made of 32 x 32 MFMA blocks.  Operands may be stored with the
+// contraction index contiguous (tile kept as [row][64 k], read from LDS with 16-byte loads; rows
+// padded to 144 bytes, and written in row pairs (r, r+8), so that neither the fragment reads nor
+// the staging writes collide on banks) or with the contraction index strided (tile kept as
+// [64 k][row], read with the LDS transpose load ds_read_b64_tr_b16; rows padded by 64 bytes), so
+// forward (x W), input-gradient (dY W^T) and weight-gradient (X^T dY) products all read the
+// tensors as they lie in memory, without transposed copies.
+// Weight-gradient products have small M x N and very long K: they are split along K over the
+// grid into fp32 partials that a second kernel adds in a fixed order.
 //
 // Lane layouts of the MFMA (wavefront lane l, 64 lanes):
 //   A fragment: row l%32, k = 8*(l/32) .. +7 ; B fragment: column l%32, same k ;
