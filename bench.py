@@ -168,6 +168,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="lm20m")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gemm-tile", default="", help="tuning: force the MFMA GEMM tile, e.g. 256x128x1 (tile M x tile N x LDS buffers)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the simulated workers are replicas on HIP streams of "
@@ -183,6 +184,8 @@ def main():
     import paper_2401_09135_amd as A
 
     w = I.workload(args.workload)
+    if args.gemm_tile:
+        A.set_gemm_tile(*[int(x) for x in args.gemm_tile.split("x")])
     k, N = w["k"], w["N"]
     n_rounds = args.warmup + args.steps
     n_events = n_rounds * N

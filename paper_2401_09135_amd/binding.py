@@ -109,6 +109,11 @@ def prof_enable(on) -> None:
     _check(lib.als_prof_enable(int(on)))
 
 
+def set_gemm_tile(bm: int, bn: int, nbuf: int) -> None:
+    """Tuning hook: force the MFMA GEMM tile (0, 0, 0 = automatic) wherever the shape allows it."""
+    _check(lib.als_k_set_gemm_tile(bm, bn, nbuf))
+
+
 def prof_collect(max_entries: int = 64):
     """[(kernel name, launches, total ms, total flops)] of the MFMA GEMM launches since enable."""
     ids = np.zeros(max_entries, np.int32)
