@@ -470,13 +470,14 @@ int gemm_mfma(const GemmDesc& g, hipStream_t st) {
   // Tile choice (measured on MI355X): the single-buffered 128x128 variant, 3 workgroups per CU
   // so that one's prologue/epilogue hides behind another's MFMAs, for short K and few tiles;
   // the double-buffered one once K is long enough to amortise its single resident pair;
-  // 256x128 (less operand traffic per flop) when there are enough tiles to fill the chip.
+  // 256x128 (less operand traffic and fewer LDS bytes per flop) when its tiles fill at least
+  // 7/8 of the 512 resident slots (2 per CU).
   int bm = 128, bn = 128, nbuf = 1;
   if (g_force_bm && fits(g.M, g.N, g_force_bm, g_force_bn)) { bm = g_force_bm; bn = g_force_bn; nbuf = g_force_nbuf; }
   else if (g.a_layout == 1) {
     if (fits(g.M, g.N, 256, 128) && (g.M / 256) * (g.N / 128) >= 128) { bm = 256; bn = 128; nbuf = 1; }
     else nbuf = 2;
-  } else if (fits(g.M, g.N, 256, 128) && (g.M / 256) * (g.N / 128) >= 1024) { bm = 256; bn = 128; }
+  } else if (fits(g.M, g.N, 256, 128) && (g.M / 256) * (g.N / 128) >= 448) { bm = 256; bn = 128; }
   else if (g.K >= 2048) nbuf = 2;
   MfmaArgs a;
   a.A = (const bf16*)g.A; a.B = (const bf16*)g.B; a.lda = g.lda; a.ldb = g.ldb;
