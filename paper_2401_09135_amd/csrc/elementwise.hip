@@ -800,8 +800,8 @@ __global__ __launch_bounds__(256) void cross_entropy_kernel(const float* __restr
   }
 }
 
-// Same, reading the row once: each thread keeps up to 32 logits (8 float4) in registers, so a
-// block of BS threads covers V <= 32 BS.
+// Same, reading the row once: each thread keeps up to 32 logits in registers, so a block of BS
+// threads covers V <= 32 BS (V a multiple of 8).
 template <typename OT, int BS>
 __global__ __launch_bounds__(BS) void cross_entropy_reg_kernel(const float* __restrict__ logits,
                                                                const int32_t* __restrict__ tok,
@@ -812,29 +812,35 @@ __global__ __launch_bounds__(BS) void cross_entropy_reg_kernel(const float* __re
   int b = t / S, s = t % S;
   int tgt = tok[(int64_t)b * (S + 1) + s + 1];
   tgt = tgt < 0 ? 0 : (tgt >= V ? V - 1 : tgt);
+  // a lane owns 8 consecutive columns per slot (two 16-byte loads, one 16-byte bf16 store)
   const f32x4* lr = reinterpret_cast<const f32x4*>(logits + (int64_t)t * V);
-  const int v4 = V / 4;
-  f32x4 x[8];
+  const int v8 = V / 8;
+  f32x4 x[4][2];
   float mx = -INFINITY;
 #pragma unroll
-  for (int i = 0; i < 8; i++) {
+  for (int i = 0; i < 4; i++) {
     int c = threadIdx.x + i * BS;
-    if (c < v4) {
-      x[i] = lr[c];
-      mx = fmaxf(fmaxf(mx, fmaxf(x[i][0], x[i][1])), fmaxf(x[i][2], x[i][3]));
+    if (c < v8) {
+#pragma unroll
+      for (int q = 0; q < 2; q++) {
+        x[i][q] = lr[2 * c + q];
+        mx = fmaxf(fmaxf(mx, fmaxf(x[i][q][0], x[i][q][1])), fmaxf(x[i][q][2], x[i][q][3]));
+      }
     }
   }
   mx = block_reduce(mx, true, sh);
   float sum = 0.0f;
 #pragma unroll
-  for (int i = 0; i < 8; i++) {
+  for (int i = 0; i < 4; i++) {
     int c = threadIdx.x + i * BS;
-    if (c < v4) {
+    if (c < v8) {
 #pragma unroll
-      for (int e = 0; e < 4; e++) {
-        x[i][e] = expf(x[i][e] - mx);
-        sum += x[i][e];
-      }
+      for (int q = 0; q < 2; q++)
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+          x[i][q][e] = expf(x[i][q][e] - mx);
+          sum += x[i][q][e];
+        }
     }
   }
   sum = block_reduce(sum, false, sh);
@@ -842,18 +848,25 @@ __global__ __launch_bounds__(BS) void cross_entropy_reg_kernel(const float* __re
   if (threadIdx.x == 0) loss_row[t] = mx + logf(sum) - logits[(int64_t)t * V + tgt];
   OT* dr = dl + (int64_t)t * V;
 #pragma unroll
-  for (int i = 0; i < 8; i++) {
+  for (int i = 0; i < 4; i++) {
     int c = threadIdx.x + i * BS;
-    if (c < v4) {
-      float4 p = make_float4(x[i][0] * inv, x[i][1] * inv, x[i][2] * inv, x[i][3] * inv);
-      int k = tgt - 4 * c;
-      if (k == 0) p.x -= 1.0f;
-      if (k == 1) p.y -= 1.0f;
-      if (k == 2) p.z -= 1.0f;
-      if (k == 3) p.w -= 1.0f;
-      p.x *= invT; p.y *= invT; p.z *= invT; p.w *= invT;
-      if (sizeof(OT) == 2) store_bf16x4(reinterpret_cast<bf16*>(dr) + 4 * c, p);
-      else reinterpret_cast<float4*>(dr)[c] = p;
+    if (c < v8) {
+      float p[8];
+#pragma unroll
+      for (int e = 0; e < 8; e++) {
+        p[e] = x[i][e >> 2][e & 3] * inv;
+        if (8 * c + e == tgt) p[e] -= 1.0f;
+        p[e] *= invT;
+      }
+      if (sizeof(OT) == 2) {
+        bf16x8 o;
+#pragma unroll
+        for (int e = 0; e < 8; e++) o[e] = (bf16)p[e];
+        *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16*>(dr) + 8 * c) = o;
+      } else {
+        reinterpret_cast<float4*>(dr)[2 * c] = make_float4(p[0], p[1], p[2], p[3]);
+        reinterpret_cast<float4*>(dr)[2 * c + 1] = make_float4(p[4], p[5], p[6], p[7]);
+      }
     }
   }
 }
@@ -862,7 +875,7 @@ int cross_entropy(const float* logits, const int32_t* tok, float* loss_row, void
                   int dl_bf16, int B, int S, int V, hipStream_t st) {
   int T = B * S;
   float invT = 1.0f / (float)T;
-  if (dl_bf16 && V % 4 == 0 && V <= 32 * 1024) {
+  if (dl_bf16 && V % 8 == 0 && V <= 32 * 1024) {
     if (V <= 32 * 256)
       hipLaunchKernelGGL((cross_entropy_reg_kernel<bf16, 256>), dim3(T), dim3(256), 0, st, logits, tok,
                          loss_row, (bf16*)dlogits, S, V, invT);
