@@ -401,6 +401,7 @@ __global__ __launch_bounds__(256, KT == 1 ? 2 : 1) void attn_bwd_dkv_kernel(cons
   float4 st4 = make_float4(0.f, 0.f, 0.f, 0.f);  // lanes 0-15: 4 lse values, lanes 16-31: 4 row dots
   auto stats_load = [&](int q_first) {
     if (tid < 32) st4 = *reinterpret_cast<const float4*>((tid < 16 ? lse_b : D_b) + q_first + 4 * (tid & 15));
+    if (tid < 16) { st4.x *= -LOG2E; st4.y *= -LOG2E; st4.z *= -LOG2E; st4.w *= -LOG2E; }  // -lse in log2 units
   };
   auto stats_store = [&](int stage) {
     if (tid < 32) *reinterpret_cast<float4*>(smem + 4 * TILE_BYTES + stage * 512 + tid * 16) = st4;
@@ -434,7 +435,6 @@ __global__ __launch_bounds__(256, KT == 1 ? 2 : 1) void attn_bwd_dkv_kernel(cons
       for (int g = 0; g < 4; g++) {
         l4[g] = *reinterpret_cast<const float4*>(Ss + (qh * 32 + 8 * g + 4 * hf) * 4);
         d4[g] = *reinterpret_cast<const float4*>(Ss + 256 + (qh * 32 + 8 * g + 4 * hf) * 4);
-        l4[g].x *= -LOG2E; l4[g].y *= -LOG2E; l4[g].z *= -LOG2E; l4[g].w *= -LOG2E;
       }
       const int roff = (qh * 32 + (lane & 31)) * ROW_D + hf * 16;
       bf16x8 qa[4], ga[4];
@@ -463,17 +463,26 @@ __global__ __launch_bounds__(256, KT == 1 ? 2 : 1) void attn_bwd_dkv_kernel(cons
           dp = MFMA(ga[kk], vf[kt][kk], dp);
         }
         const bool need_mask = qs < kw + kt * 32 + 31;
+        if (need_mask) {  // wave-uniform: only blocks that cross the diagonal pay for the compare
 #pragma unroll
-        for (int v = 0; v < 16; v++) {
-          const float lv = reinterpret_cast<const float*>(&l4[v >> 2])[v & 3];
-          const float dvv = reinterpret_cast<const float*>(&d4[v >> 2])[v & 3];
-          float p = fast_exp2(fmaf(s[v], scale_log2, lv));
-          if (need_mask) {
+          for (int v = 0; v < 16; v++) {
+            const float lv = reinterpret_cast<const float*>(&l4[v >> 2])[v & 3];
+            const float dvv = reinterpret_cast<const float*>(&d4[v >> 2])[v & 3];
+            float p = fast_exp2(fmaf(s[v], scale_log2, lv));
             int qi = qs + 8 * (v >> 2) + 4 * hf + (v & 3);
             if (key > qi) p = 0.0f;
+            s[v] = p;
+            dp[v] = p * (dp[v] - dvv);
           }
-          s[v] = p;
-          dp[v] = p * (dp[v] - dvv);
+        } else {
+#pragma unroll
+          for (int v = 0; v < 16; v++) {
+            const float lv = reinterpret_cast<const float*>(&l4[v >> 2])[v & 3];
+            const float dvv = reinterpret_cast<const float*>(&d4[v >> 2])[v & 3];
+            float p = fast_exp2(fmaf(s[v], scale_log2, lv));
+            s[v] = p;
+            dp[v] = p * (dp[v] - dvv);
+          }
         }
 #pragma unroll
         for (int kk = 0; kk < 2; kk++) {
