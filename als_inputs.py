@@ -57,6 +57,10 @@ WORKLOADS = {
                     speeds=[1.0, 1.5, 2.0, 3.0], H=5, N=4, n_events=8),
     "mini_bf16_ln": dict(_COMMON, L=2, d=256, h=4, ff=1024, V=1024, S=128, B=4, dtype="bf16", norm="layer",
                          k=4, speeds=[1.0, 1.2, 1.6, 2.4], H=10, N=4, n_events=4),
+    # bf16 mode on shapes no MFMA kernel accepts (T = 72, head width 32, V = 200): the generic
+    # GEMM / attention kernels with bf16 operands
+    "ragged_bf16": dict(_COMMON, L=2, d=64, h=2, ff=128, V=200, S=24, B=3, dtype="bf16",
+                        k=2, speeds=[1.0, 2.0], H=2, N=2, n_events=4),
     "wide_attn_f32": dict(_COMMON, L=2, d=64, h=4, dh=32, ff=128, V=200, S=24, B=3, dtype="f32",
                           k=2, speeds=[1.0, 2.0], H=2, N=2, n_events=4),
     # the 150M-class architecture on one 1024-token sequence per step (d 896 = 7 x 128, 14 heads,

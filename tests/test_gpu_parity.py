@@ -44,7 +44,8 @@ def _per_tensor_rel(g, ref, w):
 
 @pytest.mark.parametrize("name,flags", [("tiny", 0), ("mini_f32", 0), ("mini_bf16", 1), ("mini_bf16", 0),
                                         ("wide_attn_f32", 0), ("paper20m", 0), ("paper60m", 0),
-                                        ("paper60m", 1), ("paper150m", 0), ("tiny_ln", 0), ("mini_bf16_ln", 0)])
+                                        ("paper60m", 1), ("paper150m", 0), ("tiny_ln", 0), ("mini_bf16_ln", 0),
+                                        ("ragged_bf16", 0)])
 def test_loss_and_gradient_one_batch(name, flags):
     w = I.workload(name)
     theta0 = I.theta0(lm.param_layout(w), w["seed"])
@@ -69,7 +70,7 @@ def test_loss_and_gradient_one_batch(name, flags):
 @pytest.mark.parametrize("name,flags", [("tiny", 0), ("mini_f32", 0), ("mini_bf16", 1), ("mini_bf16", 0),
                                         ("mini_bf16_k16", 0), ("tiny_grace_c", 0), ("mini_bf16_grace_c", 0),
                                         ("wide_attn_f32", 0), ("paper20m", 0), ("paper60m", 0),
-                                        ("tiny_ln", 0), ("mini_bf16_ln", 0)])
+                                        ("tiny_ln", 0), ("mini_bf16_ln", 0), ("ragged_bf16", 0)])
 def test_async_run_matches_oracle(name, flags):
     w = I.workload(name)
     theta0 = I.theta0(lm.param_layout(w), w["seed"])
