@@ -486,17 +486,32 @@ int gemm_mfma(const GemmDesc& g, hipStream_t st) {
   a.split_stride = 0; a.nsplit = 1;
   int nsplit = 1;
   if (g.a_layout == 1 && g.b_layout == 0 && g.ldc == g.N) {
-    // weight-gradient shape: few tiles, long K.  Split K so the grid covers the chip, as far
-    // as the workspace allows; each split keeps at least 512 of K.
-    int tiles = a.tiles_m * a.tiles_n;
-    int want = (512 + tiles - 1) / tiles;  // about two workgroups per CU
-    int maxk = g.K / 512;
-    size_t per = (size_t)g.M * g.N * sizeof(float);
-    int maxws = g.ws ? (int)(g.ws_bytes / per) : 1;
-    nsplit = want < maxk ? want : maxk;
-    if (nsplit > maxws) nsplit = maxws;
-    if (nsplit < 1) nsplit = 1;
-    while (nsplit > 1 && (g.K % (nsplit * BK))) nsplit--;
+    // Weight-gradient shape: few tiles, long K.  K is split so that the grid fills the chip in
+    // whole rounds of its resident workgroups (2 per CU for the double-buffered 128x128 variant
+    // and for 256x128, 3 per CU for the single-buffered 128x128 one).  Candidates are costed in
+    // microseconds with measured rates: the product at 700 TFLOP/s times the round-up loss of
+    // the last round, plus the fp32 partials written and read back at 4 TB/s; each split keeps
+    // at least 512 of K and the partials must fit the workspace.
+    const size_t per = (size_t)g.M * g.N * sizeof(float);
+    const int maxws = g.ws ? (int)(g.ws_bytes / per) : 1;
+    const double t_prod = 2.0 * g.M * g.N * (double)g.K / 700e6;  // us
+    double best = 1e30;
+    int best_nbuf = nbuf, best_ns = 1;
+    for (int cand = 0; cand < (bm == 128 && !g_force_bm ? 2 : 1); cand++) {
+      const int nb = cand == 0 ? nbuf : (nbuf == 2 ? 1 : 2);
+      const int slots = 256 * ((bm == 128 && nb == 1) ? 3 : 2);
+      const int tiles = a.tiles_m * a.tiles_n;
+      for (int ns = 1; ns <= 64 && ns <= maxws; ns++) {
+        if (g.K % (ns * BK) || (ns > 1 && g.K / ns < 512)) continue;
+        const int wgs = tiles * ns;
+        const int rounds = (wgs + slots - 1) / slots;
+        double cost = t_prod * rounds * slots / wgs + (ns > 1 ? ns * (double)per * 2.0 / 4e6 : 0.0);
+        if (cand == 1) cost *= 1.03;  // prefer the first choice on near ties
+        if (cost < best) { best = cost; best_nbuf = nb; best_ns = ns; }
+      }
+    }
+    nbuf = best_nbuf;
+    nsplit = best_ns;
   }
   if (nsplit > 1) {
     a.K = g.K / nsplit; a.nsplit = nsplit;
