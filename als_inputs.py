@@ -23,16 +23,16 @@ _COMMON = dict(lr=1e-3, wd=0.1, beta1=0.9, beta2=0.999, adam_eps=1e-8, norm_eps=
                outer_lr=0.7, outer_beta=0.9, dn_c=0.0, tau_grace=0.0, zipf_a=1.1, seed=0)
 
 WORKLOADS = {
-    # BASELINE configs[0]: fp32 correctness case, 3 outer rounds = 12 sync events.
+    # benchmark configs[0]: fp32 correctness case, 3 outer rounds = 12 sync events.
     "tiny": dict(_COMMON, L=2, d=64, h=2, ff=256, V=256, S=32, B=8, dtype="f32", k=4,
                  speeds=[1.0, 1.5, 2.0, 3.0], H=5, N=4, n_events=12),
-    # BASELINE configs[1]: the 20M-class LM the headline metric is quoted on.
+    # benchmark configs[1]: the 20M-class LM the headline metric is quoted on.
     "lm20m": dict(_COMMON, L=6, d=512, h=8, ff=2048, V=8192, S=512, B=32, dtype="bf16", k=4,
                   speeds=[1.0, 1.2, 1.6, 2.4], H=50, N=4, n_events=4),
-    # BASELINE configs[3]: 150M-class LM; speeds drawn U[1,3] from the seed.
+    # benchmark configs[3]: 150M-class LM; speeds drawn U[1,3] from the seed.
     "lm150m": dict(_COMMON, L=12, d=896, h=14, ff=3584, V=32000, S=1024, B=16, dtype="bf16",
                    k=4, speeds=("uniform", 1.0, 3.0), H=50, N=4, n_events=4),
-    # BASELINE configs[4]: 16 simulated workers sharing the GPU; speeds U[1,4].
+    # benchmark configs[4]: 16 simulated workers sharing the GPU; speeds U[1,4].
     "lm20m_k16": dict(_COMMON, L=6, d=512, h=8, ff=2048, V=8192, S=512, B=32, dtype="bf16",
                       k=16, speeds=("uniform", 1.0, 4.0), H=50, N=16, n_events=16),
     # Reduced cases for parity tests (same architecture class, sizes the oracle finishes in
@@ -64,10 +64,10 @@ WORKLOADS = {
     "wide_attn_f32": dict(_COMMON, L=2, d=64, h=4, dh=32, ff=128, V=200, S=24, B=3, dtype="f32",
                           k=2, speeds=[1.0, 2.0], H=2, N=2, n_events=4),
     # the 150M-class architecture on one 1024-token sequence per step (d 896 = 7 x 128, 14 heads,
-    # V 32000, S 1024): every kernel shape class of BASELINE configs[3] at 1/16 of its batch
+    # V 32000, S 1024): every kernel shape class of benchmark configs[3] at 1/16 of its batch
     "lm150m_b1": dict(_COMMON, L=12, d=896, h=14, ff=3584, V=32000, S=1024, B=1, dtype="bf16",
                       k=2, speeds=[1.0, 2.0], H=2, N=2, n_events=2),
-    # 16 heterogeneous workers (BASELINE configs[4]'s scheduling shape) on the reduced model
+    # 16 heterogeneous workers (benchmark configs[4]'s scheduling shape) on the reduced model
     "mini_bf16_k16": dict(_COMMON, L=2, d=256, h=4, ff=1024, V=1024, S=128, B=2, dtype="bf16",
                           k=16, speeds=("uniform", 1.0, 4.0), H=6, N=16, n_events=16),
     # grace period > 0 and momentum activation c > 0 (the paper's ablation knobs), fp32 and bf16
@@ -79,7 +79,7 @@ WORKLOADS = {
                      k=3, speeds=[1.0, 2.0, 2.0], H=4, N=3, n_events=6),
 }
 
-# BASELINE configs[2]: the outer-step microbenchmark on a flat fp32 vector.
+# benchmark configs[2]: the outer-step microbenchmark on a flat fp32 vector.
 OUTER_MICROBENCH = dict(P=150_000_000, replicas=(4, 8, 16), N=(1, 4, 8), sigma=0.02,
                         drift_sigma=1e-3, outer_lr=0.7, outer_beta=0.9, seed=0)
 

@@ -97,7 +97,7 @@ def cpu_baseline(w, seconds_hint=20.0):
 
 
 def outer_microbench(args):
-    """BASELINE configs[2]: pseudo-gradient + Delayed Nesterov (single events, the grouped pass with
+    """Benchmark configs[2]: pseudo-gradient + Delayed Nesterov (single events, the grouped pass with
     fused restart) and fused AdamW on a 150M-element fp32 vector; achieved HBM GB/s from the
     algorithmic bytes per parameter (DN: 24 non-boundary, 32 boundary, grouped G events with
     restart 8G + 24 + 10G; AdamW: 30 with fp32 gradient and bf16 copy)."""

@@ -214,7 +214,7 @@ def test_attention_mfma_matches_generic_kernel_closely():
 
 @pytest.mark.timeout(900)
 def test_outer_step_microbench_vector_full_size():
-    """BASELINE configs[2]: 150M-element fp32 vector, 4 replicas, N = 4, one grouped pass ending
+    """Benchmark configs[2]: 150M-element fp32 vector, 4 replicas, N = 4, one grouped pass ending
     on the momentum update, and one AdamW step, all compared element by element."""
     mb = I.OUTER_MICROBENCH
     P, G, N = mb["P"], 4, 4

@@ -21,7 +21,7 @@ def _rel(a, b):
 
 
 def _record(line):
-    """Keep the measured parity figures of a GPU run (copied back with gpurun_out/)."""
+    """Keep the measured parity figures of a GPU run in the run's output folder, if there is one."""
     import os
     d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
     if os.path.isdir(d):
@@ -175,7 +175,7 @@ def test_full_size_150m_architecture_one_sequence():
 
 @pytest.mark.timeout(1500)
 def test_full_size_lm20m_step_in_bench_launch_configuration():
-    """BASELINE configs[1] at full size, launched as bench.py launches it (4 workers stepping
+    """Benchmark configs[1] at full size, launched as bench.py launches it (4 workers stepping
     concurrently on 4 streams): worker 0's gradient, loss and first AdamW step against the
     oracle; the other workers' first losses against oracle forward passes."""
     w = I.workload("lm20m")
