@@ -89,7 +89,8 @@ int rmsnorm_bwd_blocks(int T);
 int rmsnorm_bwd(const float* dy, const float* x, const float* rstd, const float* g,
                 const float* dx_in, float* dx_out, void* dx_lp, int lp_bf16, float* dg,
                 float* partial, int T, int d, int center, hipStream_t st);
-int cross_entropy(const float* logits, const int32_t* tok, float* loss_row, void* dlogits,
+// logits fp32 or bf16; dlogits may be the same buffer as the logits when the two types are equal
+int cross_entropy(const void* logits, int logits_bf16, const int32_t* tok, float* loss_row, void* dlogits,
                   int dl_bf16, int B, int S, int V, hipStream_t st);
 int mean_rows(const float* loss_row, float* out, int T, hipStream_t st);
 // Orders each step's input positions by token id (see elementwise.hip); offset is

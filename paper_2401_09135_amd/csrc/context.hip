@@ -17,7 +17,7 @@ struct Worker {
   bf16* lp;
   std::vector<float*> x, xm, rstd1, rstd2, lse;
   std::vector<void*> a, qkv, o, b, u, gl;
-  void* xf; float* rstdf; float* logits; void* dlogits; float* loss_row;
+  void* xf; float* rstdf; float* logits; void* dlogits; float* loss_row;  // logits: fp32 mode only
   float *dxa, *dxb, *dtmp, *Dbuf, *partial;
   void *dx_lp, *dff, *d_o, *dqkv;
   float* losses_dev; float* losses_host;
@@ -78,7 +78,8 @@ void carve(als_ctx* c, Carver& cv) {
       w.b[l] = cv.act(T * d, bf); w.u[l] = cv.act(T * ff, bf); w.gl[l] = cv.act(T * ff, bf);
     }
     w.xf = cv.act(T * d, bf); w.rstdf = cv.f32(T);
-    w.logits = cv.f32(T * V); w.dlogits = cv.act(T * V, bf); w.loss_row = cv.f32(T);
+    // bf16 mode: the output GEMM writes bf16 logits into dlogits and the cross-entropy runs in place
+    w.logits = bf ? nullptr : cv.f32(T * V); w.dlogits = cv.act(T * V, bf); w.loss_row = cv.f32(T);
     w.dxa = cv.f32(T * d); w.dxb = cv.f32(T * d); w.dtmp = cv.f32(T * d); w.Dbuf = cv.f32(BhS);
     w.partial = cv.f32((int64_t)rmsnorm_bwd_blocks((int)T) * d);
     w.dx_lp = cv.act(T * d, bf); w.dff = cv.act(T * ff, bf); w.d_o = cv.act(T * da, bf);
@@ -152,8 +153,9 @@ int forward(als_ctx* c, Worker& w, const int32_t* tok, float* loss_out) {
     RUN(gemm(f2, mf, st));
   }
   RUN(rmsnorm_fwd(w.x[g.n_layers], w.theta + L.gf, w.xf, w.rstdf, T, d, eps, c->bf, ln, st));
-  RUN(gemm(desc(c, w.xf, 0, d, wptr(c, w, L.Wout), 0, V, T, V, d, w.logits, V, false), mf, st));
-  RUN(cross_entropy(w.logits, tok, w.loss_row, w.dlogits, c->bf, B, S, V, st));
+  void* logits = c->bf ? w.dlogits : (void*)w.logits;
+  RUN(gemm(desc(c, w.xf, 0, d, wptr(c, w, L.Wout), 0, V, T, V, d, logits, V, true), mf, st));
+  RUN(cross_entropy(logits, c->bf, tok, w.loss_row, w.dlogits, c->bf, B, S, V, st));
   RUN(mean_rows(w.loss_row, loss_out, T, st));
   return ALS_OK;
 }

@@ -757,8 +757,10 @@ int rmsnorm_bwd(const float* dy, const float* x, const float* rstd, const float*
 }
 
 // ------------------------------------------------------------------------------------------
-// Softmax cross-entropy on fp32 logits, one block per row: loss_row = logsumexp - logit[target];
-// dlogits = (softmax - onehot) / T.
+// Softmax cross-entropy, one block per row: loss_row = logsumexp - logit[target];
+// dlogits = (softmax - onehot) / T.  Logits are fp32, or bf16 (the bf16 path: the output GEMM
+// rounds them like every other activation); dlogits may overwrite the logits (same pointer, same
+// element type): every element is read before it is written, by the thread that writes it.
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ float block_reduce(float v, bool is_max, float* sh) {
   int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -772,29 +774,28 @@ __device__ __forceinline__ float block_reduce(float v, bool is_max, float* sh) {
   return r;
 }
 
-template <typename OT>
-__global__ __launch_bounds__(256) void cross_entropy_kernel(const float* __restrict__ logits,
-                                                            const int32_t* __restrict__ tok,
-                                                            float* __restrict__ loss_row,
-                                                            OT* __restrict__ dl, int S, int V,
+template <typename IT, typename OT>
+__global__ __launch_bounds__(256) void cross_entropy_kernel(const IT* logits, const int32_t* __restrict__ tok,
+                                                            float* __restrict__ loss_row, OT* dl, int S, int V,
                                                             float invT) {
   __shared__ float sh[8];
   int t = blockIdx.x;
   int b = t / S, s = t % S;
   int tgt = tok[(int64_t)b * (S + 1) + s + 1];
   tgt = tgt < 0 ? 0 : (tgt >= V ? V - 1 : tgt);
-  const float* lr = logits + (int64_t)t * V;
+  const IT* lr = logits + (int64_t)t * V;
+  const float ltgt = (float)lr[tgt];
   float mx = -INFINITY;
-  for (int c = threadIdx.x; c < V; c += blockDim.x) mx = fmaxf(mx, lr[c]);
+  for (int c = threadIdx.x; c < V; c += blockDim.x) mx = fmaxf(mx, (float)lr[c]);
   mx = block_reduce(mx, true, sh);
   float sum = 0.0f;
-  for (int c = threadIdx.x; c < V; c += blockDim.x) sum += expf(lr[c] - mx);
-  sum = block_reduce(sum, false, sh);
+  for (int c = threadIdx.x; c < V; c += blockDim.x) sum += expf((float)lr[c] - mx);
+  sum = block_reduce(sum, false, sh);   // its barriers also order the read of lr[tgt] before the writes below
   float lse = mx + logf(sum);
-  if (threadIdx.x == 0) loss_row[t] = lse - lr[tgt];
+  if (threadIdx.x == 0) loss_row[t] = lse - ltgt;
   OT* dr = dl + (int64_t)t * V;
   for (int c = threadIdx.x; c < V; c += blockDim.x) {
-    float p = expf(lr[c] - lse);
+    float p = expf((float)lr[c] - lse);
     if (c == tgt) p -= 1.0f;
     dr[c] = (OT)(p * invT);
   }
@@ -802,18 +803,18 @@ __global__ __launch_bounds__(256) void cross_entropy_kernel(const float* __restr
 
 // Same, reading the row once: each thread keeps up to 32 logits in registers, so a block of BS
 // threads covers V <= 32 BS (V a multiple of 8).
-template <typename OT, int BS>
-__global__ __launch_bounds__(BS) void cross_entropy_reg_kernel(const float* __restrict__ logits,
-                                                               const int32_t* __restrict__ tok,
-                                                               float* __restrict__ loss_row,
-                                                               OT* __restrict__ dl, int S, int V, float invT) {
+template <typename IT, typename OT, int BS>
+__global__ __launch_bounds__(BS) void cross_entropy_reg_kernel(const IT* logits, const int32_t* __restrict__ tok,
+                                                               float* __restrict__ loss_row, OT* dl, int S, int V,
+                                                               float invT) {
   __shared__ float sh[16];
   int t = blockIdx.x;
   int b = t / S, s = t % S;
   int tgt = tok[(int64_t)b * (S + 1) + s + 1];
   tgt = tgt < 0 ? 0 : (tgt >= V ? V - 1 : tgt);
-  // a lane owns 8 consecutive columns per slot (two 16-byte loads, one 16-byte bf16 store)
-  const f32x4* lr = reinterpret_cast<const f32x4*>(logits + (int64_t)t * V);
+  // a lane owns 8 consecutive columns per slot (16-byte loads, one 16-byte bf16 store)
+  const IT* row = logits + (int64_t)t * V;
+  const float ltgt = (float)row[tgt];
   const int v8 = V / 8;
   f32x4 x[4][2];
   float mx = -INFINITY;
@@ -821,11 +822,17 @@ __global__ __launch_bounds__(BS) void cross_entropy_reg_kernel(const float* __re
   for (int i = 0; i < 4; i++) {
     int c = threadIdx.x + i * BS;
     if (c < v8) {
+      if (sizeof(IT) == 2) {
+        bf16x8 r = reinterpret_cast<const bf16x8*>(row)[c];
 #pragma unroll
-      for (int q = 0; q < 2; q++) {
-        x[i][q] = lr[2 * c + q];
-        mx = fmaxf(fmaxf(mx, fmaxf(x[i][q][0], x[i][q][1])), fmaxf(x[i][q][2], x[i][q][3]));
+        for (int e = 0; e < 8; e++) x[i][e >> 2][e & 3] = (float)r[e];
+      } else {
+        x[i][0] = reinterpret_cast<const f32x4*>(row)[2 * c];
+        x[i][1] = reinterpret_cast<const f32x4*>(row)[2 * c + 1];
       }
+#pragma unroll
+      for (int q = 0; q < 2; q++)
+        mx = fmaxf(fmaxf(mx, fmaxf(x[i][q][0], x[i][q][1])), fmaxf(x[i][q][2], x[i][q][3]));
     }
   }
   mx = block_reduce(mx, true, sh);
@@ -845,7 +852,7 @@ __global__ __launch_bounds__(BS) void cross_entropy_reg_kernel(const float* __re
   }
   sum = block_reduce(sum, false, sh);
   float inv = 1.0f / sum;
-  if (threadIdx.x == 0) loss_row[t] = mx + logf(sum) - logits[(int64_t)t * V + tgt];
+  if (threadIdx.x == 0) loss_row[t] = mx + logf(sum) - ltgt;
   OT* dr = dl + (int64_t)t * V;
 #pragma unroll
   for (int i = 0; i < 4; i++) {
@@ -871,26 +878,31 @@ __global__ __launch_bounds__(BS) void cross_entropy_reg_kernel(const float* __re
   }
 }
 
-int cross_entropy(const float* logits, const int32_t* tok, float* loss_row, void* dlogits,
+int cross_entropy(const void* logits, int logits_bf16, const int32_t* tok, float* loss_row, void* dlogits,
                   int dl_bf16, int B, int S, int V, hipStream_t st) {
   int T = B * S;
   float invT = 1.0f / (float)T;
+  if (logits_bf16 && !dl_bf16) return set_error(ALS_ERR_INVALID, "cross_entropy: bf16 logits need bf16 dlogits");
   if (dl_bf16 && V % 8 == 0 && V <= 32 * 1024) {
-    if (V <= 32 * 256)
-      hipLaunchKernelGGL((cross_entropy_reg_kernel<bf16, 256>), dim3(T), dim3(256), 0, st, logits, tok,
-                         loss_row, (bf16*)dlogits, S, V, invT);
-    else
-      hipLaunchKernelGGL((cross_entropy_reg_kernel<bf16, 1024>), dim3(T), dim3(1024), 0, st, logits, tok,
-                         loss_row, (bf16*)dlogits, S, V, invT);
+    const bool big = V > 32 * 256;
+#define ALS_CE_LAUNCH(IT, BS)                                                                               \
+  hipLaunchKernelGGL((cross_entropy_reg_kernel<IT, bf16, BS>), dim3(T), dim3(BS), 0, st, (const IT*)logits, \
+                     tok, loss_row, (bf16*)dlogits, S, V, invT)
+    if (logits_bf16) { if (big) ALS_CE_LAUNCH(bf16, 1024); else ALS_CE_LAUNCH(bf16, 256); }
+    else             { if (big) ALS_CE_LAUNCH(float, 1024); else ALS_CE_LAUNCH(float, 256); }
+#undef ALS_CE_LAUNCH
     ALS_CHECK_LAUNCH();
     return ALS_OK;
   }
-  if (dl_bf16)
-    hipLaunchKernelGGL(cross_entropy_kernel<bf16>, dim3(T), dim3(256), 0, st, logits, tok, loss_row,
-                       (bf16*)dlogits, S, V, invT);
+  if (logits_bf16)
+    hipLaunchKernelGGL((cross_entropy_kernel<bf16, bf16>), dim3(T), dim3(256), 0, st, (const bf16*)logits, tok,
+                       loss_row, (bf16*)dlogits, S, V, invT);
+  else if (dl_bf16)
+    hipLaunchKernelGGL((cross_entropy_kernel<float, bf16>), dim3(T), dim3(256), 0, st, (const float*)logits, tok,
+                       loss_row, (bf16*)dlogits, S, V, invT);
   else
-    hipLaunchKernelGGL(cross_entropy_kernel<float>, dim3(T), dim3(256), 0, st, logits, tok, loss_row,
-                       (float*)dlogits, S, V, invT);
+    hipLaunchKernelGGL((cross_entropy_kernel<float, float>), dim3(T), dim3(256), 0, st, (const float*)logits, tok,
+                       loss_row, (float*)dlogits, S, V, invT);
   ALS_CHECK_LAUNCH();
   return ALS_OK;
 }
