@@ -17,8 +17,8 @@
  *     and nothing aborts; als_last_error() returns the text of the calling thread's last
  *     error.
  *   - "dev" pointers are device (HBM) addresses, "host" pointers are host addresses.
- *   - The library never allocates device memory except in the als_k_* test entry points'
- *     callers' own buffers: als_init() carves everything out of one caller-owned arena.
+ *   - The library never allocates device memory: als_init() carves everything out of one
+ *     caller-owned arena, and the als_k_* entry points work on the caller's buffers only.
  *     Streams are borrowed hipStream_t handles passed as void*.
  *   - Flat parameter vector layout (row-major tensors, fp32), P elements in total:
  *       E [V,d], Ppos [S,d], per layer: Wqkv [d,3a] (columns q|k|v, head-major inside each,
@@ -27,8 +27,9 @@
  *       g2 [d]; finally gf [d].  The first P_decay elements (everything but the gains) are
  *       weight-decayed.
  *   - Model (reading of "decoder-only transformer", appendix "Network Architecture"):
- *     pre-norm blocks, RMSNorm, causal softmax attention scaled by 1/sqrt(d/h), tanh-GELU FFN,
- *     learned positions, no bias, untied output matrix, loss averaged over B*S positions.
+ *     pre-norm blocks, RMSNorm (or gain-only LayerNorm, norm_kind), causal softmax attention
+ *     scaled by 1/sqrt(head width), tanh-GELU FFN, learned positions, no bias, untied output
+ *     matrix, loss averaged over B*S positions.
  */
 #ifndef ALS_H
 #define ALS_H
@@ -47,7 +48,8 @@ extern "C" {
 #define ALS_ERR_STATE (-4)   /* call not valid in the context's current state */
 
 #define ALS_DTYPE_F32 0  /* fp32 everywhere (debug / reference mode) */
-#define ALS_DTYPE_BF16 1 /* bf16 GEMM and attention operands, fp32 accumulate, master, optimiser */
+#define ALS_DTYPE_BF16 1 /* bf16 GEMM and attention operands and activations between them (logits
+                            included), fp32 accumulation, residual stream, master weights, optimiser */
 #define ALS_NORM_RMS 0
 #define ALS_NORM_LAYER 1
 
@@ -107,7 +109,8 @@ int als_destroy(als_ctx* ctx);
  * next batch, backward, AdamW with this step's learning rate).  AdamW moments and step
  * count persist across calls and restarts.
  *   tokens_dev: int32 [n_steps, B, S+1] on the device, values in [0, V) (ids outside the range
- *     are clamped into it, never dereferenced); position s predicts s+1.  lr_host: n_steps floats (host), read before the call returns.
+ *     are clamped into it, never dereferenced); position s predicts s+1.  lr_host: n_steps
+ *     floats (host), read before the call returns.
  *   loss_host_or_null: if non-null receives the n_steps mean losses and the call waits for
  *     the worker's stream; if null the call only enqueues work (fetch the losses later with
  *     als_get_losses after als_sync).  Does not touch server state. */
@@ -227,8 +230,8 @@ int als_k_gemm_ex(const void* A, const void* B, void* C, int M, int N, int K, in
                   void* C2, const void* U, void* ws_dev, size_t ws_bytes, void* stream);
 /* Benchmark hooks.  als_prof_enable(n), n >= 1, makes every n-th MFMA GEMM launch record a HIP
  * event before and after itself on its own stream (a timed launch costs about 20 us of host
- * time and orders the stream around it, so a throughput run samples); 0 switches it off; als_prof_collect waits for the device and returns, per
- * kernel instantiation (id), the number of launches, their summed duration in ms and their
+ * time and orders the stream around it, so a throughput run samples); 0 switches it off;
+ * als_prof_collect waits for the device and returns, per kernel instantiation (id), the number of launches, their summed duration in ms and their
  * summed algorithmic FLOPs (2 M N K), then forgets them.  Returns the number of entries
  * written (<= max_entries) or a negative error.  als_prof_kernel_name writes the kernel's
  * template name for an id. */
