@@ -74,20 +74,19 @@ __device__ __forceinline__ bf16x8 lds_read_tr(const char* p, int stride) {
   return __builtin_bit_cast(bf16x8, r);
 }
 
-// tanh through the hardware exp2 and reciprocal: 1 - 2 / (1 + e^{2y}); absolute error of a
-// few 1e-7, far below the bf16 rounding of the values it multiplies
-__device__ __forceinline__ float fast_tanh(float y) {
-  float e = __builtin_amdgcn_exp2f(y * 2.8853900817779268f);  // e^{2y}
-  return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + e);
-}
-// gelu_tanh(u) and its derivative from one tanh
+// gelu_tanh(u) = 0.5 u (1 + tanh y), y = a u (1 + b u^2), equals u sigma(2y) with sigma(z) =
+// 1 / (1 + e^-z); its derivative is sigma + u sigma (1 - sigma) 2y', 2y' = 2a (1 + 3b u^2).  One
+// hardware exp2 and one reciprocal give sigma (absolute error of a few 1e-7, far below the bf16
+// rounding of the stored values); 9 more VALU operations give both outputs.  u -> -inf: e = inf,
+// sigma = 0, both outputs 0; u -> +inf: sigma = 1, outputs u and 1.
 __device__ __forceinline__ void gelu_both(float u, float& val, float& grad) {
-  const float a = 0.7978845608028654f, b = 0.044715f;
+  const float a = 0.7978845608028654f, b = 0.044715f, log2e = 1.4426950408889634f;
+  const float k1 = -2.0f * log2e * a, k2 = k1 * b, k3 = 2.0f * a, k4 = 6.0f * a * b;
   float u2 = u * u;
-  float th = fast_tanh(a * u * (1.0f + b * u2));
-  float hp = 0.5f * (1.0f + th);
-  val = u * hp;
-  grad = hp + 0.5f * u * (1.0f - th * th) * a * (1.0f + 3.0f * b * u2);
+  float e = __builtin_amdgcn_exp2f(u * fmaf(k2, u2, k1));  // e^{-2y}
+  float sg = __builtin_amdgcn_rcpf(1.0f + e);
+  val = u * sg;
+  grad = fmaf(val * (1.0f - sg), fmaf(k4, u2, k3), sg);
 }
 
 struct MfmaArgs {
