@@ -85,7 +85,10 @@ int rmsnorm_fwd(const float* x, const float* g, void* y, float* rstd, int T, int
                 int out_bf16, int center, hipStream_t st);
 // dx_out = (dx_in ? dx_in : 0) + rmsnorm_backward(dy); optional low-precision copy of dx_out;
 // dg = sum over rows of dy * xhat (uses partial[nblk*d] scratch, nblk = rmsnorm_bwd_blocks()).
+// With dg == nullptr only the partials are left, for one rmsnorm_dg_sum() over nset consecutive
+// sets of partials into nset consecutive gain gradients.
 int rmsnorm_bwd_blocks(int T);
+int rmsnorm_dg_sum(const float* partial, float* dg, int T, int d, int nset, hipStream_t st);
 int rmsnorm_bwd(const float* dy, const float* x, const float* rstd, const float* g,
                 const float* dx_in, float* dx_out, void* dx_lp, int lp_bf16, float* dg,
                 float* partial, int T, int d, int center, hipStream_t st);

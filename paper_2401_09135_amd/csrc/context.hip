@@ -81,7 +81,8 @@ void carve(als_ctx* c, Carver& cv) {
     // bf16 mode: the output GEMM writes bf16 logits into dlogits and the cross-entropy runs in place
     w.logits = bf ? nullptr : cv.f32(T * V); w.dlogits = cv.act(T * V, bf); w.loss_row = cv.f32(T);
     w.dxa = cv.f32(T * d); w.dxb = cv.f32(T * d); w.dtmp = cv.f32(T * d); w.Dbuf = cv.f32(BhS);
-    w.partial = cv.f32((int64_t)rmsnorm_bwd_blocks((int)T) * d);
+    // one set of gain-gradient partials per norm, in the layout order of the gains (g1, g2 per layer, gf)
+    w.partial = cv.f32((int64_t)(2 * g.n_layers + 1) * rmsnorm_bwd_blocks((int)T) * d);
     w.dx_lp = cv.act(T * d, bf); w.dff = cv.act(T * ff, bf); w.d_o = cv.act(T * da, bf);
     w.dqkv = cv.act(T * 3 * da, bf);
     w.losses_dev = cv.f32(g.max_local_steps);
@@ -172,8 +173,10 @@ int backward(als_ctx* c, Worker& w, const int32_t* tok, int slot) {
   // output matrix and final norm
   RUN(gemm(desc_dw(c, w, w.xf, d, w.dlogits, V, d, V, T, w.grad + L.Wout), mf, st));
   RUN(gemm(desc(c, w.dlogits, 0, V, wptr(c, w, L.Wout), 1, V, T, d, V, w.dtmp, d, false), mf, st));
+  // the norms leave their gain-gradient partials; one kernel adds all of them after the last layer
+  const int64_t pset = (int64_t)rmsnorm_bwd_blocks(T) * d;
   RUN(rmsnorm_bwd(w.dtmp, w.x[nl], w.rstdf, w.theta + L.gf, nullptr, w.dxa, w.dx_lp, c->bf,
-                  w.grad + L.gf, w.partial, T, d, ln, st));
+                  nullptr, w.partial + 2 * nl * pset, T, d, ln, st));
   for (int l = nl - 1; l >= 0; l--) {
     // feed-forward block: x_next = xm + gelu(b W1) W2
     RUN(gemm(desc_dw(c, w, w.gl[l], ff, w.dx_lp, d, ff, d, T, w.grad + L.W2[l]), mf, st));
@@ -183,7 +186,7 @@ int backward(als_ctx* c, Worker& w, const int32_t* tok, int slot) {
     RUN(gemm(desc_dw(c, w, w.b[l], d, w.dff, ff, d, ff, T, w.grad + L.W1[l]), mf, st));
     RUN(gemm(desc(c, w.dff, 0, ff, wptr(c, w, L.W1[l]), 1, ff, T, d, ff, w.dtmp, d, false), mf, st));
     RUN(rmsnorm_bwd(w.dtmp, w.xm[l], w.rstd2[l], w.theta + L.g2[l], w.dxa, w.dxb, w.dx_lp, c->bf,
-                    w.grad + L.g2[l], w.partial, T, d, ln, st));
+                    nullptr, w.partial + (2 * l + 1) * pset, T, d, ln, st));
     // attention block: xm = x + attn(a Wqkv) Wo
     RUN(gemm(desc_dw(c, w, w.o[l], da, w.dx_lp, d, da, d, T, w.grad + L.Wo[l]), mf, st));
     RUN(gemm(desc(c, w.dx_lp, 0, d, wptr(c, w, L.Wo[l]), 1, d, T, da, d, w.d_o, da, true), mf, st));
@@ -194,8 +197,9 @@ int backward(als_ctx* c, Worker& w, const int32_t* tok, int slot) {
     RUN(gemm(desc_dw(c, w, w.a[l], d, w.dqkv, 3 * da, d, 3 * da, T, w.grad + L.Wqkv[l]), mf, st));
     RUN(gemm(desc(c, w.dqkv, 0, 3 * da, wptr(c, w, L.Wqkv[l]), 1, 3 * da, T, d, 3 * da, w.dtmp, d, false), mf, st));
     RUN(rmsnorm_bwd(w.dtmp, w.x[l], w.rstd1[l], w.theta + L.g1[l], w.dxb, w.dxa, w.dx_lp, c->bf,
-                    w.grad + L.g1[l], w.partial, T, d, ln, st));
+                    nullptr, w.partial + 2 * l * pset, T, d, ln, st));
   }
+  RUN(rmsnorm_dg_sum(w.partial, w.grad + L.g1[0], T, d, 2 * nl + 1, st));
   // w.dtmp (T x d floats) is free again here: scratch for the embedding gradient's chunk partials
   RUN(embed_bwd(tok, w.sort_offset + (int64_t)slot * (V + 1), w.sort_pos + (int64_t)slot * T, w.dxa,
                 w.grad + L.E, w.grad + L.Ppos, w.dtmp, B, S, d, V, st));

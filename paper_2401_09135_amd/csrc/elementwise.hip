@@ -700,12 +700,15 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(
     partial[(int64_t)blockIdx.x * d + c] = smem[c] + smem[d + c] + smem[2 * d + c] + smem[3 * d + c];
 }
 
-// out[c] = sum_b partial[b][c]: 32 columns per block, 32 row groups each adding every 32nd
-// partial (8 independent loads in flight: the kernel is pure load latency), combined in a fixed
-// order.
+// out[j][c] = sum_b partial[j][b][c] for nset consecutive sets of partials (blockIdx.y = j; the
+// outputs are consecutive rows of d floats): 32 columns per block, 32 row groups each adding
+// every 32nd partial (8 independent loads in flight: the kernel is pure load latency), combined
+// in a fixed order.
 __global__ __launch_bounds__(1024) void sum_partials_kernel(const float* __restrict__ partial,
                                                             float* __restrict__ out, int nblk, int d) {
   __shared__ float sh[32][33];
+  partial += (int64_t)blockIdx.y * nblk * d;
+  out += (int64_t)blockIdx.y * d;
   int cl = threadIdx.x & 31, rg = threadIdx.x >> 5;
   int c = blockIdx.x * 32 + cl;
   float acc = 0.0f;
@@ -751,7 +754,13 @@ int rmsnorm_bwd(const float* dy, const float* x, const float* rstd, const float*
   }
 #undef ALS_NORM_BWD
   ALS_CHECK_LAUNCH();
-  hipLaunchKernelGGL(sum_partials_kernel, dim3((d + 31) / 32), dim3(1024), 0, st, partial, dg, nblk, d);
+  if (dg) return rmsnorm_dg_sum(partial, dg, T, d, 1, st);
+  return ALS_OK;
+}
+
+int rmsnorm_dg_sum(const float* partial, float* dg, int T, int d, int nset, hipStream_t st) {
+  hipLaunchKernelGGL(sum_partials_kernel, dim3((d + 31) / 32, nset), dim3(1024), 0, st, partial, dg,
+                     rmsnorm_bwd_blocks(T), d);
   ALS_CHECK_LAUNCH();
   return ALS_OK;
 }
