@@ -21,11 +21,11 @@ def _rel(a, b):
 
 
 def _record(line):
-    """Keep the measured parity figures of a GPU run in the run's output folder, if there is one."""
+    """Append a measured parity figure to the file named by ALS_PARITY_LOG, if that is set."""
     import os
-    d = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-    if os.path.isdir(d):
-        with open(os.path.join(d, "parity_metrics.txt"), "a") as f:
+    path = os.environ.get("ALS_PARITY_LOG")
+    if path:
+        with open(path, "a") as f:
             f.write(line + "\n")
 
 
