@@ -77,6 +77,17 @@ WORKLOADS = {
                               k=4, speeds=[1.0, 1.2, 1.6, 2.4], H=10, N=4, n_events=8, tau_grace=0.5, dn_c=0.25),
     "mini_f32": dict(_COMMON, L=2, d=128, h=4, ff=384, V=320, S=48, B=3, dtype="f32",
                      k=3, speeds=[1.0, 2.0, 2.0], H=4, N=3, n_events=6),
+    # edge shapes for parity tests: an odd vocabulary (no vector-width kernel applies to the logits),
+    # the largest model width the norm kernels take, heads of 32 in bf16 mode (MFMA GEMMs with the
+    # generic attention kernels), and sequences of a single position
+    "edge_v_odd": dict(_COMMON, L=1, d=64, h=2, ff=128, V=201, S=16, B=2, dtype="bf16",
+                       k=2, speeds=[1.0, 2.0], H=2, N=2, n_events=2),
+    "edge_d1024": dict(_COMMON, L=1, d=1024, h=16, ff=1024, V=256, S=128, B=1, dtype="bf16",
+                       k=2, speeds=[1.0, 2.0], H=2, N=2, n_events=2),
+    "edge_dh32_bf16": dict(_COMMON, L=2, d=128, h=4, ff=256, V=256, S=128, B=2, dtype="bf16",
+                           k=2, speeds=[1.0, 2.0], H=2, N=2, n_events=2),
+    "edge_s1": dict(_COMMON, L=1, d=64, h=2, ff=64, V=64, S=1, B=4, dtype="f32",
+                    k=2, speeds=[1.0, 2.0], H=2, N=2, n_events=2),
 }
 
 # benchmark configs[2]: the outer-step microbenchmark on a flat fp32 vector.

@@ -45,8 +45,12 @@ def _per_tensor_rel(g, ref, w):
 @pytest.mark.parametrize("name,flags", [("tiny", 0), ("mini_f32", 0), ("mini_bf16", 1), ("mini_bf16", 0),
                                         ("wide_attn_f32", 0), ("paper20m", 0), ("paper60m", 0),
                                         ("paper60m", 1), ("paper150m", 0), ("tiny_ln", 0), ("mini_bf16_ln", 0),
-                                        ("ragged_bf16", 0)])
+                                        ("ragged_bf16", 0), ("edge_v_odd", 0), ("edge_d1024", 0),
+                                        ("edge_dh32_bf16", 0), ("edge_s1", 0)])
 def test_loss_and_gradient_one_batch(name, flags):
+    # (edge_s1, sequences of one position, is compared here only: with a single key the query and
+    # key gradients are zero in exact arithmetic, AdamW turns their rounding noise into steps of
+    # the size of the learning rate, and a whole run is then not comparable element by element)
     w = I.workload(name)
     theta0 = I.theta0(lm.param_layout(w), w["seed"])
     # move off the initial point a little so every path carries signal
@@ -70,7 +74,8 @@ def test_loss_and_gradient_one_batch(name, flags):
 @pytest.mark.parametrize("name,flags", [("tiny", 0), ("mini_f32", 0), ("mini_bf16", 1), ("mini_bf16", 0),
                                         ("mini_bf16_k16", 0), ("tiny_grace_c", 0), ("mini_bf16_grace_c", 0),
                                         ("wide_attn_f32", 0), ("paper20m", 0), ("paper60m", 0),
-                                        ("tiny_ln", 0), ("mini_bf16_ln", 0), ("ragged_bf16", 0)])
+                                        ("tiny_ln", 0), ("mini_bf16_ln", 0), ("ragged_bf16", 0),
+                                        ("edge_v_odd", 0)])
 def test_async_run_matches_oracle(name, flags):
     w = I.workload(name)
     theta0 = I.theta0(lm.param_layout(w), w["seed"])
