@@ -86,6 +86,10 @@ WORKLOADS = {
                        k=2, speeds=[1.0, 2.0], H=2, N=2, n_events=2),
     "edge_dh32_bf16": dict(_COMMON, L=2, d=128, h=4, ff=256, V=256, S=128, B=2, dtype="bf16",
                            k=2, speeds=[1.0, 2.0], H=2, N=2, n_events=2),
+    # 20 workers of equal speed: every round ends in ONE tie group of 20 events, more than the 16 a
+    # single pass of the fused outer kernel takes
+    "tiny_k20": dict(_COMMON, L=1, d=64, h=2, ff=64, V=64, S=8, B=2, dtype="f32", k=20,
+                     speeds=[1.0] * 20, H=2, N=20, n_events=40),
     "edge_s1": dict(_COMMON, L=1, d=64, h=2, ff=64, V=64, S=1, B=4, dtype="f32",
                     k=2, speeds=[1.0, 2.0], H=2, N=2, n_events=2),
 }
