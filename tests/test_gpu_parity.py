@@ -140,6 +140,39 @@ def test_adam_state_persists_and_group_call_equals_single_calls():
         assert np.array_equal(a, b)
 
 
+def test_set_vector_and_staleness_helpers():
+    """als_set_vector on a bf16-mode replica refreshes its bf16 working copy (the next loss is the
+    oracle's at the NEW parameters); als_worker_staleness counts server events since the replica
+    (re)started."""
+    w = I.workload("mini_bf16")
+    theta0 = I.theta0(lm.param_layout(w), w["seed"])
+    rng = np.random.default_rng(3)
+    theta1 = theta0 + (rng.standard_normal(theta0.size) * 0.02).astype(np.float32)
+    tok = _stream(w)(0).take(1)[0]
+    dev = torch.from_numpy(tok).to("cuda:0")
+    ctx = A.Context(A.Config.from_workload(w), theta0)
+    loss_before, _ = ctx.worker_loss_grad(1, dev)
+    ctx.set_vector("worker_theta", 1, theta1)
+    assert np.array_equal(ctx.get_vector("worker_theta", 1), theta1)
+    assert np.array_equal(ctx.get_vector("worker_theta", 0), theta0)
+    loss_after, g = ctx.worker_loss_grad(1, dev)
+    r0 = float(lm.forward(theta0, tok, w, keep=False)[0])
+    r1, rg = lm.loss_and_grad(theta1.copy(), tok, w)
+    assert abs(loss_before - r0) / r0 < TOL["bf16"]["loss"]
+    assert abs(loss_after - r1) / r1 < TOL["bf16"]["loss"]
+    assert abs(r1 - r0) / r0 > 10 * TOL["bf16"]["loss"]          # the two points are told apart
+    assert _rel(g, rg) < 1.5e-2
+    assert [ctx.staleness(i) for i in range(w["k"])] == [0] * w["k"]
+    ctx.outer_apply_dn([0], restart=True)
+    assert [ctx.staleness(i) for i in range(w["k"])] == [0, 1, 1, 1]
+    ctx.outer_apply_dn([1], restart=False)
+    assert [ctx.staleness(i) for i in range(w["k"])] == [1, 2, 2, 2]
+    ctx.outer_apply_dn([2, 3], restart=True)
+    assert [ctx.staleness(i) for i in range(w["k"])] == [3, 4, 0, 0]
+    assert ctx.staleness(99) == -1
+    ctx.close()
+
+
 def test_error_paths_return_codes():
     w = I.workload("tiny")
     theta0 = I.theta0(lm.param_layout(w), 0)
