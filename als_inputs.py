@@ -90,6 +90,9 @@ WORKLOADS = {
     # single pass of the fused outer kernel takes
     "tiny_k20": dict(_COMMON, L=1, d=64, h=2, ff=64, V=64, S=8, B=2, dtype="f32", k=20,
                      speeds=[1.0] * 20, H=2, N=20, n_events=40),
+    # a vocabulary beyond the 32768 columns the register-resident cross-entropy kernel holds
+    "edge_v_big": dict(_COMMON, L=1, d=64, h=2, ff=64, V=40000, S=8, B=2, dtype="bf16",
+                       k=2, speeds=[1.0, 2.0], H=2, N=2, n_events=2),
     "edge_s1": dict(_COMMON, L=1, d=64, h=2, ff=64, V=64, S=1, B=4, dtype="f32",
                     k=2, speeds=[1.0, 2.0], H=2, N=2, n_events=2),
 }

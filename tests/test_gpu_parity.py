@@ -46,7 +46,7 @@ def _per_tensor_rel(g, ref, w):
                                         ("wide_attn_f32", 0), ("paper20m", 0), ("paper60m", 0),
                                         ("paper60m", 1), ("paper150m", 0), ("tiny_ln", 0), ("mini_bf16_ln", 0),
                                         ("ragged_bf16", 0), ("edge_v_odd", 0), ("edge_d1024", 0),
-                                        ("edge_dh32_bf16", 0), ("edge_s1", 0)])
+                                        ("edge_dh32_bf16", 0), ("edge_s1", 0), ("edge_v_big", 0)])
 def test_loss_and_gradient_one_batch(name, flags):
     # (edge_s1, sequences of one position, is compared here only: with a single key the query and
     # key gradients are zero in exact arithmetic, AdamW turns their rounding noise into steps of
