@@ -93,6 +93,9 @@ WORKLOADS = {
     # a vocabulary beyond the 32768 columns the register-resident cross-entropy kernel holds
     "edge_v_big": dict(_COMMON, L=1, d=64, h=2, ff=64, V=40000, S=8, B=2, dtype="bf16",
                        k=2, speeds=[1.0, 2.0], H=2, N=2, n_events=2),
+    # a single worker (the asynchronous schedule degenerates to a chain of rounds), buffer N = 2
+    "tiny_k1": dict(_COMMON, L=1, d=64, h=2, ff=64, V=64, S=8, B=2, dtype="f32", k=1,
+                    speeds=[1.5], H=3, N=2, n_events=4),
     "edge_s1": dict(_COMMON, L=1, d=64, h=2, ff=64, V=64, S=1, B=4, dtype="f32",
                     k=2, speeds=[1.0, 2.0], H=2, N=2, n_events=2),
 }

@@ -75,7 +75,7 @@ def test_loss_and_gradient_one_batch(name, flags):
                                         ("mini_bf16_k16", 0), ("tiny_grace_c", 0), ("mini_bf16_grace_c", 0),
                                         ("wide_attn_f32", 0), ("paper20m", 0), ("paper60m", 0),
                                         ("tiny_ln", 0), ("mini_bf16_ln", 0), ("ragged_bf16", 0),
-                                        ("edge_v_odd", 0), ("tiny_k20", 0)])
+                                        ("edge_v_odd", 0), ("tiny_k20", 0), ("tiny_k1", 0)])
 def test_async_run_matches_oracle(name, flags):
     w = I.workload(name)
     theta0 = I.theta0(lm.param_layout(w), w["seed"])
