@@ -171,7 +171,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="lm20m")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--streams", type=int, default=0, help="HIP streams the workers share (worker i on stream i mod n); 0 = one per worker")
+    ap.add_argument("--streams", type=int, default=0, help="HIP streams the workers share (worker i on stream i mod n); 0 = min(k, 4): the box gives a process 4 hardware queues")
     ap.add_argument("--gemm-tile", default="", help="tuning: force the MFMA GEMM tile, e.g. 256x128x1 (tile M x tile N x LDS buffers)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -198,7 +198,7 @@ def main():
     # parameter layout from the library itself; values N(0, 0.02), gains 1
     P, Pd = A.param_count(cfg), A.param_count_decayed(cfg)
     theta0 = I.theta0([("decayed", (Pd,), "matrix"), ("gains", (P - Pd,), "gain")], w["seed"])
-    ctx = A.Context(cfg, theta0, n_streams=args.streams or None)
+    ctx = A.Context(cfg, theta0, n_streams=args.streams or min(k, 4))
 
     # how many local rounds each worker starts: the first one plus one per sync event of its own
     rounds = [1 + int((ev_w == i).sum()) for i in range(k)]
