@@ -173,6 +173,26 @@ def test_set_vector_and_staleness_helpers():
     ctx.close()
 
 
+@pytest.mark.parametrize("name", ["mini_bf16", "mini_bf16_k16"])
+def test_whole_run_is_bit_reproducible(name):
+    """Two runs of the same asynchronous schedule, workers overlapping on their streams, give the
+    same bits: every dependency is an event and no kernel uses floating-point atomics, so results do
+    not depend on how the streams happen to interleave."""
+    w = I.workload(name)
+    theta0 = I.theta0(lm.param_layout(w), w["seed"])
+    outs = []
+    for n_streams in (None, 1):      # one stream per worker, then everything on one stream
+        cfg = A.Config.from_workload(w, max_local_steps=w["H"])
+        ctx = A.Context(cfg, theta0, n_streams=n_streams)
+        got = A.run_async(w, theta0, _stream(w), ctx=ctx)
+        outs.append((got["theta"], got["m"], got["delta"], [np.asarray(l) for l in got["losses"]]))
+        ctx.close()
+    for a, b in zip(outs[0][:3], outs[1][:3]):
+        assert np.array_equal(a, b)
+    for la, lb in zip(outs[0][3], outs[1][3]):
+        assert np.array_equal(la, lb)
+
+
 def test_error_paths_return_codes():
     w = I.workload("tiny")
     theta0 = I.theta0(lm.param_layout(w), 0)
