@@ -13,7 +13,7 @@ from . import binding as A
 T = 16384   # tokens per worker step (32 sequences of 512)
 # name, M, N, K, a_layout, b_layout, epilogue (-1: plain store to fp32, 0: store bf16, 1 residual, 2 GELU, 3 x derivative)
 SHAPES = [("qkv", T, 1536, 512, 0, 0, 0), ("wo+res", T, 512, 512, 0, 0, 1), ("ffn1+gelu", T, 2048, 512, 0, 0, 2),
-          ("ffn2+res", T, 512, 2048, 0, 0, 1), ("head", T, 8192, 512, 0, 0, -1),
+          ("ffn2+res", T, 512, 2048, 0, 0, 1), ("head bf16", T, 8192, 512, 0, 0, 0),
           ("dffn2*gp", T, 2048, 512, 0, 1, 3), ("dffn1 f32", T, 512, 2048, 0, 1, -1), ("dqkv f32", T, 512, 1536, 0, 1, -1),
           ("do bf16", T, 512, 512, 0, 1, 0), ("dhead f32", T, 512, 8192, 0, 1, -1),
           ("dw ffn1", 512, 2048, T, 1, 0, 0), ("dw ffn2", 2048, 512, T, 1, 0, 0), ("dw qkv", 512, 1536, T, 1, 0, 0),
