@@ -244,7 +244,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16* __restrict
 // workgroup per (128 queries, head, sample).  Per 64-key tile:
 //   S^T = K Q^T ; dP^T = V dO^T ; dS^T = P^T (dP^T - D) ; dQ^T += K^T dS^T
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ o,
+__global__ __launch_bounds__(256, 3) void attn_bwd_dq_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ o,
                                                           const bf16* __restrict__ d_o,
                                                           const float* __restrict__ lse, float* __restrict__ D,
                                                           bf16* __restrict__ dqkv, int S, int h, int B, float scale) {
@@ -317,13 +317,6 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16* __restr
           s = MFMA(kfr[kk], qf[kk], s);
           dp = MFMA(vfr[kk], gf[kk], dp);
         }
-#pragma unroll
-        for (int kk = 0; kk < 2; kk++)
-#pragma unroll
-          for (int dt = 0; dt < 2; dt++) {
-            int off = tr_off(lane, kt * 32 + 16 * kk, dt * 32);
-            ktr[kk][dt] = lds_tr2(Ks + off, Ks + off + 8 * ROW_D);
-          }
         __builtin_amdgcn_sched_barrier(0);
         if (need_mask) {
 #pragma unroll
@@ -337,6 +330,13 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(const bf16* __restr
 #pragma unroll
           for (int v = 0; v < 16; v++) s[v] = fast_exp2(fmaf(s[v], scale_log2, -lse2)) * (dp[v] - Dq);
         }
+#pragma unroll
+        for (int kk = 0; kk < 2; kk++)
+#pragma unroll
+          for (int dt = 0; dt < 2; dt++) {
+            int off = tr_off(lane, kt * 32 + 16 * kk, dt * 32);
+            ktr[kk][dt] = lds_tr2(Ks + off, Ks + off + 8 * ROW_D);
+          }
 #pragma unroll
         for (int kk = 0; kk < 2; kk++) {
           bf16x8 dsf = pack8(s, kk);
