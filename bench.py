@@ -78,17 +78,17 @@ def cpu_baseline(w, seconds_hint=20.0):
     from oracle.optim import AdamW
     threads, blas = _host_threads()
     nb = max(1, w["B"] // 8)
-    toks = I.TokenStream(w["seed"], 0, w["B"], w["S"], w["V"]).take(3)
+    toks = I.TokenStream(w["seed"], 0, w["B"], w["S"], w["V"]).take(6)
     while True:
         theta = I.theta0(lm.param_layout(w), w["seed"])
         opt = AdamW(theta.size, np.float32, w["beta1"], w["beta2"], w["adam_eps"], w["wd"], lm.n_decayed(w))
         n, t0 = 0, time.perf_counter()
-        while True:             # whole steps on the sample until about 10 s are spent (3 at most)
+        while True:             # whole steps on the sample until about 10 s are spent (6 at most)
             _loss, grad = lm.loss_and_grad(theta, toks[n][:nb], w)
             opt.step(theta, grad, w["lr"])
             n += 1
             dt = time.perf_counter() - t0
-            if dt >= 10.0 or n == 3 or (n == 1 and dt < 2.5 and nb < w["B"]):
+            if dt >= 10.0 or n == 6 or (n == 1 and dt < 2.5 and nb < w["B"]):
                 break
         if dt >= 8.0 or nb >= w["B"]:
             break
