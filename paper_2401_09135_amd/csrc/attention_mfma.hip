@@ -197,8 +197,21 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16* __restrict
           for (int v = 0; v < 16; v++) mx = fmaxf(mx, s[kt][v]);
       }
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run, mx);   // finite: key 0 is visible to every query
-      const float neg = -m_new * scale_log2;
+      // The reference point m_run only has to keep the exponentials in range, it need not be the
+      // exact running maximum: it moves (and the accumulators are rescaled) only when some row's
+      // maximum has grown by more than 2^8 in probability units since it was last set.  The first
+      // tile always sets it (m_run = -inf; key 0 is visible to every query, so mx is finite).
+      if (__any((mx - m_run) * scale_log2 > 8.0f)) {  // wave-uniform
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = fast_exp2((m_run - m_new) * scale_log2);
+        l_run *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < 2; dt++)
+#pragma unroll
+          for (int v = 0; v < 16; v++) oacc[dt][v] *= alpha;
+        m_run = m_new;
+      }
+      const float neg = -m_run * scale_log2;
       float lsum = 0.0f;
 #pragma unroll
       for (int kt = 0; kt < 2; kt++)
@@ -208,15 +221,6 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const bf16* __restrict
           s[kt][v] = p;
           lsum += p;
         }
-      if (__any(m_new != m_run)) {  // wave-uniform: rescale only when some row's maximum moved
-        const float alpha = fast_exp2((m_run - m_new) * scale_log2);
-        l_run *= alpha;
-#pragma unroll
-        for (int dt = 0; dt < 2; dt++)
-#pragma unroll
-          for (int v = 0; v < 16; v++) oacc[dt][v] *= alpha;
-        m_run = m_new;
-      }
       l_run += lsum;
 #pragma unroll
       for (int kt = 0; kt < 2; kt++)

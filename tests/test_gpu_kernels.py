@@ -109,10 +109,10 @@ def test_gemm_generic(M, N, K, al, bl, dt):
     np.testing.assert_allclose(c.cpu().numpy(), ar @ br, rtol=1e-5, atol=1e-4)
 
 
-def _attention_case(B, S, h, dh, dt, use_mfma):
+def _attention_case(B, S, h, dh, dt, use_mfma, scale=1.0):
     rng = np.random.default_rng(S + dh)
     d = h * dh
-    qkv = _dev(rng.standard_normal((B * S, 3 * d)).astype(np.float32), dt)
+    qkv = _dev(rng.standard_normal((B * S, 3 * d)).astype(np.float32) * scale, dt)
     d_o = _dev(rng.standard_normal((B * S, d)).astype(np.float32) * 0.1, dt)
     o = torch.empty(B * S, d, dtype=dt, device=DEV)
     lse = torch.empty(B * h * S, dtype=torch.float32, device=DEV)
@@ -201,6 +201,17 @@ def test_attention_mfma(B, S, h):
     d = h * 64
     for nm, sl in (("dq", slice(0, d)), ("dk", slice(d, 2 * d)), ("dv", slice(2 * d, 3 * d))):
         assert _rel(dq[:, sl], rdq[:, sl]) < 1.5e-2, nm
+
+
+@pytest.mark.parametrize("scale", [3.0, 0.05])
+def test_attention_mfma_score_ranges(scale):
+    """Scores with a standard deviation of 9 (the running reference point of the online softmax must
+    move several times along a row, by more than its 2^8 slack) and nearly constant scores."""
+    o, ro, lse, rlse, dq, rdq = _attention_case(2, 512, 2, 64, torch.bfloat16, True, scale=scale)
+    assert np.isfinite(o).all() and np.isfinite(dq).all()
+    assert _rel(o, ro) < 1e-2
+    np.testing.assert_allclose(lse, rlse, rtol=1e-4, atol=1e-4)
+    assert _rel(dq, rdq) < 2e-2
 
 
 def test_attention_mfma_matches_generic_kernel_closely():
