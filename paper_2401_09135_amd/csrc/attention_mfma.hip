@@ -305,6 +305,7 @@ __global__ __launch_bounds__(256, 3) void attn_bwd_dq_kernel(const bf16* __restr
       const bool need_mask = key0 + 63 > qw;
 #pragma unroll
       for (int kt = 0; kt < 2; kt++) {
+        if (key0 + kt * 32 > qw + 31) continue;  // wave-uniform: every key of this block is masked
         f32x16 s = zero16(), dp = zero16();
         const int roff = (kt * 32 + (lane & 31)) * ROW_D + hf * 16;
         // fragment reads ahead of their MFMAs, the transposed K reads behind the score MFMAs
