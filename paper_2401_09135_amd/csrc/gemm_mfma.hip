@@ -1,9 +1,10 @@
 // bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate) for the
 // worker step's projections: C[M,N] = sum_k A(m,k) B(k,n).
 //
-// One workgroup of 4 wavefronts (2 x 2) owns a BM x BN tile of C and walks K in slices of 64
-// staged through LDS (one buffer with 2-3 workgroups per CU, or two buffers); each wavefront
-// owns a (BM/2) x (BN/2) sub-tile made of 32 x 32 MFMA blocks.  Operands may be stored with the
+// One workgroup of 4 wavefronts (2 x 2; 8 wavefronts, 2 x 4, for the 256 x 256 tile) owns a
+// BM x BN tile of C and walks K in slices of 64 staged through LDS (one buffer with 2-3
+// workgroups per CU, or two buffers); each wavefront owns a sub-tile of 64 x 64 or 128 x 64
+// made of 32 x 32 MFMA blocks.  Operands may be stored with the
 // contraction index contiguous (tile kept as [row][64 k], read from LDS with 16-byte loads; rows
 // padded to 144 bytes, and written in row pairs (r, r+8), so that neither the fragment reads nor
 // the staging writes collide on banks) or with the contraction index strided (tile kept as
@@ -45,8 +46,13 @@ int kernel_id(int bm, int bn, int al, int bl, int epi, int to_bf16, int split, i
   return (bm / 128 - 1) | (bn / 128 - 1) << 1 | al << 2 | bl << 3 | epi << 4 | to_bf16 << 6 | split << 7 | (nbuf - 1) << 8;
 }
 
+// wavefronts per workgroup: 2 x 2, or 2 x 4 for the 256 x 256 tile (each wavefront then owns a
+// 128 x 64 sub-tile, as in the 256 x 128 tile, and two wavefronts share every SIMD)
+constexpr int tile_waves(int bm, int bn) { return bm == 256 && bn == 256 ? 8 : 4; }
+
 template <int BM, int BN, int AL, int BL, int NBUF>
 struct Tile {
+  static constexpr int NT = 64 * tile_waves(BM, BN);  // threads per workgroup
   // AL == 0: A tile kept as [BM rows][64 k] ; AL == 1: as [64 k][BM rows]
   static constexpr int A_STRIDE = AL == 0 ? BK * 2 + 16 : BM * 2 + 64;
   static constexpr int A_BYTES = A_STRIDE * (AL == 0 ? BM : BK);
@@ -55,8 +61,8 @@ struct Tile {
   static constexpr int B_BYTES = B_STRIDE * (BL == 1 ? BN : BK);
   static constexpr int STAGE = A_BYTES + B_BYTES;
   static constexpr int LDS_BYTES = (NBUF == 2 ? 2 : 1) * STAGE;
-  static constexpr int A_CHUNKS = BM * BK * 2 / 16 / 256;  // 16-byte chunks per thread
-  static constexpr int B_CHUNKS = BN * BK * 2 / 16 / 256;
+  static constexpr int A_CHUNKS = BM * BK * 2 / 16 / NT;  // 16-byte chunks per thread
+  static constexpr int B_CHUNKS = BN * BK * 2 / 16 / NT;
 };
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
@@ -104,12 +110,13 @@ struct MfmaArgs {
 // tiles.  NBUF = 1: single LDS buffer, two barriers per slice, but half the LDS so that OCC
 // workgroups share a CU and one's epilogue and barrier stalls hide behind another's MFMAs.
 template <int BM, int BN, int AL, int BL, int EPI, typename TO, bool SPLIT, int NBUF, int OCC>
-__global__ __launch_bounds__(256, OCC) void gemm_mfma_kernel(MfmaArgs g) {
+__global__ __launch_bounds__(64 * tile_waves(BM, BN), OCC) void gemm_mfma_kernel(MfmaArgs g) {
   typedef Tile<BM, BN, AL, BL, NBUF> TL;
-  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
+  constexpr int NW = tile_waves(BM, BN), WGN = NW / 2;   // wavefront grid 2 x WGN
+  constexpr int WM = BM / 2, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WGN, wn = wave % WGN;
 
   // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Without split-K
   // every XCD gets a contiguous run of tiles (n fastest), so tiles sharing an A panel share an
@@ -134,7 +141,7 @@ __global__ __launch_bounds__(256, OCC) void gemm_mfma_kernel(MfmaArgs g) {
   const char* Bg = reinterpret_cast<const char*>(BL == 1 ? g.B + (int64_t)n0 * g.ldb + kbase : g.B + kbase * g.ldb + n0);
   constexpr int A_CPR = AL == 0 ? 8 : BM / 8;   // 16-byte chunks per tile row as it lies in memory
   constexpr int B_CPR = BL == 1 ? 8 : BN / 8;
-  constexpr int A_RPC = 256 / A_CPR, B_RPC = 256 / B_CPR;  // tile rows covered by 256 lanes
+  constexpr int A_RPC = TL::NT / A_CPR, B_RPC = TL::NT / B_CPR;  // tile rows covered by one pass of the workgroup
   // Lanes 8q..8q+7 move one 128-byte row piece.  For contraction-contiguous tiles (144-byte LDS
   // rows) neighbouring lane groups take rows r and r+8, whose LDS images lie 32 banks apart, so
   // the 16 lanes of one LDS write cycle touch all 64 banks once.
@@ -268,7 +275,7 @@ __global__ __launch_bounds__(256, OCC) void gemm_mfma_kernel(MfmaArgs g) {
   TO* C = reinterpret_cast<TO*>(g.C);
   if (SPLIT) C += (int64_t)zsplit * g.split_stride;
   constexpr int PITCH = WN * 4 + 16;  // rows 4 banks apart: 16-byte accesses of 16 rows, or of two row halves, never collide
-  static_assert(4 * 32 * PITCH <= TL::LDS_BYTES, "epilogue staging must fit the operand buffers");
+  static_assert(NW * 32 * PITCH <= TL::LDS_BYTES, "epilogue staging must fit the operand buffers");
   char* stg = smem + wave * (32 * PITCH);
   constexpr int CPL = sizeof(TO) == 2 ? 8 : 4;  // consecutive columns per lane
   constexpr int LPR = WN / CPL;                 // lanes per row
@@ -398,9 +405,9 @@ int launch(const MfmaArgs& a, int nsplit, hipStream_t st) {
   if (prof) {
     // start/stop events attached to the dispatch itself: their difference is the kernel's own
     // execution time, as a profiler reports it
-    hipExtLaunchKernelGGL(kern, grid, dim3(256), TL::LDS_BYTES, st, rec.e0, rec.e1, 0, a);
+    hipExtLaunchKernelGGL(kern, grid, dim3(TL::NT), TL::LDS_BYTES, st, rec.e0, rec.e1, 0, a);
   } else {
-    hipLaunchKernelGGL(kern, grid, dim3(256), TL::LDS_BYTES, st, a);
+    hipLaunchKernelGGL(kern, grid, dim3(TL::NT), TL::LDS_BYTES, st, a);
   }
   ALS_CHECK_LAUNCH();
   if (prof) {
@@ -434,7 +441,7 @@ bool gemm_mfma_supported(const GemmDesc& g) {
   return false;
 }
 
-// tile variants: 256x256 double-buffered (1 workgroup per CU), 256x128 and 128x128 either
+// tile variants: 256x256 double-buffered (8 wavefronts, 1 workgroup per CU), 256x128 and 128x128 either
 // double-buffered or single-buffered with 2 / 3 workgroups per CU
 #define ALS_TILE_SWITCH(AL, BL, EPI, TO, SPLIT)                                                            \
   do {                                                                                                     \
@@ -474,7 +481,8 @@ int gemm_mfma(const GemmDesc& g, hipStream_t st) {
   int bm = 128, bn = 128, nbuf = 1;
   if (g_force_bm && fits(g.M, g.N, g_force_bm, g_force_bn)) { bm = g_force_bm; bn = g_force_bn; nbuf = g_force_nbuf; }
   else if (g.a_layout == 1) {
-    if (fits(g.M, g.N, 256, 128) && (g.M / 256) * (g.N / 128) >= 128) { bm = 256; bn = 128; nbuf = 1; }
+    if (fits(g.M, g.N, 256, 256) && (g.M / 256) * (g.N / 256) >= 64) { bm = 256; bn = 256; nbuf = 2; }
+    else if (fits(g.M, g.N, 256, 128) && (g.M / 256) * (g.N / 128) >= 128) { bm = 256; bn = 128; nbuf = 1; }
     else nbuf = 2;
   } else if (fits(g.M, g.N, 256, 128) && (g.M / 256) * (g.N / 128) >= 448) { bm = 256; bn = 128; }
   else if (g.K >= 2048) nbuf = 2;
@@ -498,7 +506,7 @@ int gemm_mfma(const GemmDesc& g, hipStream_t st) {
     int best_nbuf = nbuf, best_ns = 1;
     for (int cand = 0; cand < (bm == 128 && !g_force_bm ? 2 : 1); cand++) {
       const int nb = cand == 0 ? nbuf : (nbuf == 2 ? 1 : 2);
-      const int slots = 256 * ((bm == 128 && nb == 1) ? 3 : 2);
+      const int slots = 256 * (bn == 256 ? 1 : (bm == 128 && nb == 1) ? 3 : 2);  // resident workgroups on the chip
       const int tiles = a.tiles_m * a.tiles_n;
       for (int ns = 1; ns <= 64 && ns <= maxws; ns++) {
         if (g.K % (ns * BK) || (ns > 1 && g.K / ns < 512)) continue;
