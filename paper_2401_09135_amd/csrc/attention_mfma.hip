@@ -449,23 +449,40 @@ __global__ __launch_bounds__(256, KT == 1 ? 2 : 1) void attn_bwd_dkv_kernel(cons
         ga[kk] = lds_direct(Gs + roff + kk * 32);
       }
       bf16x8 qT[2][2], gT[2][2];  // [kk over the 32 queries][head-dim half]
+      auto read_transposed = [&]() {
 #pragma unroll
-      for (int kk = 0; kk < 2; kk++)
+        for (int kk = 0; kk < 2; kk++)
 #pragma unroll
-        for (int dt = 0; dt < 2; dt++) {
-          int off = tr_off(lane, qh * 32 + 16 * kk, dt * 32);
-          qT[kk][dt] = lds_tr2(Qs + off, Qs + off + 8 * ROW_D);
-          gT[kk][dt] = lds_tr2(Gs + off, Gs + off + 8 * ROW_D);
-        }
+          for (int dt = 0; dt < 2; dt++) {
+            int off = tr_off(lane, qh * 32 + 16 * kk, dt * 32);
+            qT[kk][dt] = lds_tr2(Qs + off, Qs + off + 8 * ROW_D);
+            gT[kk][dt] = lds_tr2(Gs + off, Gs + off + 8 * ROW_D);
+          }
+      };
+      if (KT != 1) read_transposed();
 #pragma unroll
       for (int kt = 0; kt < KT; kt++) {
         const int key = kw + kt * 32 + (lane & 31);
         if (qs + 31 < kw + kt * 32) continue;  // wave-uniform
         f32x16 s = zero16(), dp = zero16();
+        if (KT == 1) {
+          // the 16 transpose reads for the second pair of products trickle in behind the first
+          // pair's 8 MFMAs (two per MFMA)
+          __builtin_amdgcn_sched_barrier(0);
+          read_transposed();
+        }
 #pragma unroll
         for (int kk = 0; kk < 4; kk++) {
           s = MFMA(qa[kk], kf[kt][kk], s);
           dp = MFMA(ga[kk], vf[kt][kk], dp);
+        }
+        if (KT == 1) {
+#pragma unroll
+          for (int m = 0; m < 8; m++) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+          }
+          __builtin_amdgcn_sched_barrier(0);
         }
         const bool need_mask = qs < kw + kt * 32 + 31;
         if (need_mask) {  // wave-uniform: only blocks that cross the diagonal pay for the compare
