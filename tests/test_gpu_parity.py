@@ -140,6 +140,41 @@ def test_adam_state_persists_and_group_call_equals_single_calls():
         assert np.array_equal(a, b)
 
 
+def _random_config(seed):
+    """A small valid model drawn from the seed: every dimension varies, ragged token counts included."""
+    rng = np.random.default_rng([seed, 0xC0F])
+    dh = int(rng.choice([32, 64]))
+    h = int(rng.integers(1, 5))
+    if (h * dh) % 64:
+        h += 1
+    wide = bool(rng.integers(0, 2))
+    d = h * dh if not wide else 64 * int(rng.integers(1, 4))
+    w = dict(I.WORKLOADS["tiny"], L=int(rng.integers(1, 4)), d=d, h=h, ff=64 * int(rng.integers(1, 6)),
+             V=int(rng.integers(17, 700)), S=int(rng.integers(2, 200)), B=int(rng.integers(1, 5)),
+             dtype=str(rng.choice(["f32", "bf16"])), norm=str(rng.choice(["rms", "layer"])), seed=seed)
+    if wide or d != h * dh:
+        w["dh"] = dh
+    w["name"] = f"random{seed}"
+    return w
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_loss_and_gradient_random_small_configs(seed):
+    w = _random_config(seed)
+    theta0 = I.theta0(lm.param_layout(w), seed)
+    rng = np.random.default_rng(seed)
+    theta0 = theta0 + (rng.standard_normal(theta0.size) * 0.01).astype(np.float32)
+    tok = I.TokenStream(seed, 0, w["B"], w["S"], w["V"]).take(1)[0]
+    ctx = A.Context(A.Config.from_workload(w), theta0, n_streams=1)
+    loss, g = ctx.worker_loss_grad(0, torch.from_numpy(tok).to("cuda:0"))
+    ctx.close()
+    rloss, rg = lm.loss_and_grad(theta0.copy(), tok, w)
+    bf = w["dtype"] == "bf16"
+    desc = {k: w[k] for k in ("L", "d", "h", "ff", "V", "S", "B", "dtype", "norm")}
+    assert abs(loss - rloss) / abs(rloss) < TOL[w["dtype"]]["loss"], desc
+    assert _rel(g, rg) < (2e-2 if bf else 1e-5), desc
+
+
 def test_set_vector_and_staleness_helpers():
     """als_set_vector on a bf16-mode replica refreshes its bf16 working copy (the next loss is the
     oracle's at the NEW parameters); als_worker_staleness counts server events since the replica
