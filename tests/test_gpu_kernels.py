@@ -299,6 +299,39 @@ def test_gemm_epilogues(mfma):
     np.testing.assert_allclose(d.float().cpu().numpy(), acc * u.float().cpu().numpy(), rtol=1e-2, atol=2e-2)
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_gemm_mfma_random_shapes_layouts_and_tiles(seed):
+    """Random tile-aligned shapes in every operand layout the step uses, under a randomly forced
+    tile / buffering variant (or the automatic choice), with and without split-K scratch."""
+    rng = np.random.default_rng([seed, 0x6E])
+    al, bl = [(0, 0), (0, 1), (1, 0)][int(rng.integers(0, 3))]
+    tile = [(0, 0, 0), (256, 256, 2), (256, 128, 2), (256, 128, 1), (128, 128, 2), (128, 128, 1), (128, 128, 3)][int(rng.integers(0, 7))]
+    unit_m, unit_n = max(tile[0], 128), max(tile[1], 128)
+    M, N = unit_m * int(rng.integers(1, 5)), unit_n * int(rng.integers(1, 5))
+    K = 64 * int(rng.integers(1, 48))
+    out_bf16 = bool(rng.integers(0, 2)) and al == 0
+    a = rng.standard_normal((M, K)).astype(np.float32)
+    b = rng.standard_normal((K, N)).astype(np.float32)
+    ad = _dev(a if al == 0 else a.T.copy(), torch.bfloat16)
+    bd = _dev(b if bl == 0 else b.T.copy(), torch.bfloat16)
+    ar = ad.float().cpu().numpy().astype(np.float64)
+    br = bd.float().cpu().numpy().astype(np.float64)
+    ref = (ar if al == 0 else ar.T) @ (br if bl == 0 else br.T)
+    ws = torch.empty(int(rng.integers(1, 9)) * M * N, dtype=torch.float32, device=DEV) if (al == 1 and rng.integers(0, 2)) else None
+    c = torch.full((M, N), float("nan"), dtype=torch.bfloat16 if out_bf16 else torch.float32, device=DEV)
+    try:
+        A.lib.als_k_set_gemm_tile(*tile)
+        A.k_gemm(ad, bd, c, M, N, K, al, bl, use_mfma=True, ws=ws)
+        torch.cuda.synchronize()
+    finally:
+        A.lib.als_k_set_gemm_tile(0, 0, 0)
+    what = f"M{M} N{N} K{K} layouts {al}{bl} tile {tile} bf16 out {out_bf16} scratch {None if ws is None else ws.numel() // (M * N)}"
+    if out_bf16:
+        np.testing.assert_allclose(c.float().cpu().numpy(), ref, rtol=1e-2, atol=1e-2 * np.sqrt(K / 64), err_msg=what)
+    else:
+        np.testing.assert_allclose(c.cpu().numpy(), ref, rtol=1e-4, atol=2e-3 * np.sqrt(K / 64), err_msg=what)
+
+
 def test_gemm_mfma_tile_variants_agree():
     """Every tile / buffering variant of the MFMA GEMM gives the same product."""
     M, N, K = 512, 512, 256
