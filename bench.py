@@ -1,10 +1,21 @@
 """Benchmark of the asynchronous Local-SGD hot path on one MI355X.
 
-A "step" is one outer round of the paper's asynchronous schedule on the 20M-class workload:
-N = 4 sync events (pseudo-gradient + Delayed Nesterov + restart) together with the local rounds
-(DyLU step counts 20/25/33/50, each step = forward + backward + AdamW on 32 x 512 tokens) of the
-four simulated workers, which run on their own HIP streams.  Tokens are synthetic Zipf(1.1)
-draws, resident in HBM before the clock starts.  Prints ONE JSON line.
+Headline (default run): the 150M-class workload (benchmark configs[3], the largest configuration
+that runs on one GPU).  A "step" is one outer round of the paper's asynchronous schedule: N = 4 sync
+events (pseudo-gradient + Delayed Nesterov + restart) together with the local rounds of the four
+simulated workers (DyLU step counts, each step = forward + backward + AdamW on 16 x 1024 tokens),
+which run on their own HIP streams.  Tokens are synthetic Zipf(1.1) draws, resident in HBM before the
+clock starts.  The default run then also measures the 20M-class workload (configs[1]), the same model
+with 16 workers (configs[4], with the outer-step overhead fraction) and the outer-step
+microbenchmark (configs[2]) and reports them under config.other_workloads.  Prints ONE JSON line.
+
+  python bench.py                                  the default run described above
+  python bench.py --workload lm20m                 one workload only
+  python bench.py --workload outer_microbench      configs[2] only
+  python bench.py --workload gemm_microbench [--tiles 256x128x1,128x128x2]
+                                                   the MFMA GEMM on the step's shapes, one kernel at a
+                                                   time on one stream (the program behind the counter
+                                                   runs in profiles/)
 """
 from __future__ import annotations
 
@@ -20,10 +31,12 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
-# HBM bytes per launch of the step's GEMM kernels, measured with rocprofv3 --pmc FETCH_SIZE (x 2.0)
-# and WRITE_SIZE (x 1.0) on the same shapes (profiles/gemm_mfma_microbench.md gives the commands,
-# the calibration of the two factors and the comparison with the algorithmic bytes).  Counters
-# cannot be collected from inside this process, so the figure is carried here.
+HEADLINE = "lm150m"
+# HBM bytes per launch of the dominant GEMM kernel of a workload, measured with rocprofv3 --pmc
+# FETCH_SIZE (x 2.0) and WRITE_SIZE (x 1.0) on the same shapes, one kernel at a time
+# (profiles/gemm_mfma_microbench.md gives the commands, the calibration of the two factors and the
+# comparison with the algorithmic bytes).  Counters cannot be collected from inside this process, so
+# the figure is carried here, keyed by workload and kernel; a kernel without an entry reports null.
 MEASURED_TRAFFIC_BYTES = {"lm20m": {"gemm_mfma_kernel<128, 128, 1, 0, STORE, float, true, 2, 2>": 99.0e6}}
 
 
@@ -51,7 +64,6 @@ def cpu_baseline_outer(mb):
     """The oracle's Delayed Nesterov event (pseudo-gradient + Alg. 3, numpy fp32) on the same
     150M-element vectors: two non-boundary events timed, 24 algorithmic bytes per parameter."""
     import numpy as np
-    import als_inputs as I
     from oracle.optim import DelayedNesterov, pseudo_gradient
     P = mb["P"]
     rng = np.random.default_rng(mb["seed"])
@@ -69,8 +81,8 @@ def cpu_baseline_outer(mb):
                        f"elementwise arithmetic (single-threaded), {dt:.2f} s per event on {os.cpu_count()} host cpus")
 
 
-def cpu_baseline(w, seconds_hint=20.0):
-    """The oracle as it stands, timed on the host: one local step (forward, backward, AdamW) of
+def cpu_baseline(w):
+    """The oracle as it stands, timed on the host: local steps (forward, backward, AdamW) of
     worker 0 on a slice of its batch, sized to take roughly 10-30 s."""
     import numpy as np
     import als_inputs as I
@@ -99,12 +111,11 @@ def cpu_baseline(w, seconds_hint=20.0):
                        f"BLAS {blas} with {threads} threads")
 
 
-def outer_microbench(args):
+def outer_microbench(steps):
     """Benchmark configs[2]: pseudo-gradient + Delayed Nesterov (single events, the grouped pass with
     fused restart) and fused AdamW on a 150M-element fp32 vector; achieved HBM GB/s from the
     algorithmic bytes per parameter (DN: 24 non-boundary, 32 boundary, grouped G events with
-    restart 8G + 24 + 10G; AdamW: 30 with fp32 gradient and bf16 copy)."""
-    import numpy as np
+    restart 8G + 24 + 10G; AdamW: 30 with fp32 gradient and bf16 copy).  Returns the result table."""
     import torch
     import als_inputs as I
     import paper_2401_09135_amd as A
@@ -130,7 +141,7 @@ def outer_microbench(args):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / iters
 
-    iters = max(args.steps, 20)
+    iters = max(steps, 20)
     res = {}
     # single events rotating over the 16 replicas so that nothing stays in the last-level cache
     for label, N, t0, bpp in (("dn_event_nonboundary_N4", 4, 0, 24), ("dn_event_boundary_N4", 4, 3, 32),
@@ -151,57 +162,137 @@ def outer_microbench(args):
         A.k_adamw(works[i % G], grad, am, av, lps[i % G], P - 4096, step[0], 1e-3)
     ms = timed(adam, iters)
     res["adamw_fp32grad_bf16copy"] = dict(ms=ms, bytes_per_param=30, GBps=P * 30 / ms / 1e6)
-    key = "dn_event_nonboundary_N4"
+    res["_iters"] = iters
+    del theta, m, delta, starts, works, lps, grad, am, av
+    torch.cuda.empty_cache()
+    return res
+
+
+def outer_microbench_line(args):
+    import als_inputs as I
+    mb = I.OUTER_MICROBENCH
+    res = outer_microbench(args.steps)
+    iters = res.pop("_iters")
+    # configs[2] is the fused pass over 4-16 replicas: the reported value is the grouped pass over 4
+    # workers with the restart fused in (the single events and the larger groups are in results)
+    key = "dn_group_G4_N4_restart"
     out = dict(metric="DN/AdamW HBM GB/s", value=res[key]["GBps"], unit="GB/s", n_gpus=1, steps=iters, warmup=2,
                ms_per_step=res[key]["ms"], higher_is_better=True, scaling="weak", vs_baseline=None, dtype="f32",
-               data="synthetic", config=dict(workload=f"outer_microbench: {P} fp32 parameters, 16 replicas resident, "
-                                                      "value = one non-boundary Delayed-Nesterov event (N=4, c=0)", results=res),
+               data="synthetic", config=dict(workload=f"outer_microbench: {mb['P']} fp32 parameters, 16 replicas resident, "
+                                                      "value = one fused pass of 4 Delayed-Nesterov events (N=4, c=0) "
+                                                      "with the 4 workers' restart", results=res),
                roofline=dict(bound="hbm", achieved=res[key]["GBps"], peak=PEAK_HBM_GBS, unit="GB/s",
-                             frac=res[key]["GBps"] / PEAK_HBM_GBS,
-                             # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 of this launch (profiles/outer_microbench_dn_adamw.md)
-                             traffic=(2343894 + 1171876) * 1024.0, kernel="dn_group_kernel<4>"),
+                             frac=res[key]["GBps"] / PEAK_HBM_GBS, traffic=None, kernel="dn_group_kernel"),
                cpu_baseline=None if args.no_cpu_baseline else cpu_baseline_outer(mb))
     print(json.dumps(out))
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=8)
-    ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="lm20m")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--streams", type=int, default=0, help="HIP streams the workers share (worker i on stream i mod n); 0 = min(k, 4): the box gives a process 4 hardware queues")
-    ap.add_argument("--gemm-tile", default="", help="tuning: force the MFMA GEMM tile, e.g. 256x128x1 (tile M x tile N x LDS buffers)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the simulated workers are replicas on HIP streams of "
-              "a single MI355X); --gpus must be 1", file=sys.stderr)
-        sys.exit(2)
+# name, M, N, K, a_layout, b_layout, epilogue (-1: plain store to fp32, 0: store bf16, 1 residual, 2 GELU, 3 x derivative)
+def gemm_shapes(w):
+    T, d, ff, V = w["B"] * w["S"], w["d"], w["ff"], w["V"]
+    a = w["h"] * w["dh"] if w.get("dh") else d
+    return [("qkv", T, 3 * a, d, 0, 0, 0), ("wo+res", T, d, a, 0, 0, 1), ("ffn1+gelu", T, ff, d, 0, 0, 2),
+            ("ffn2+res", T, d, ff, 0, 0, 1), ("head bf16", T, V, d, 0, 0, 0),
+            ("dffn2*gp", T, ff, d, 0, 1, 3), ("dffn1 f32", T, d, ff, 0, 1, -1), ("dqkv f32", T, d, 3 * a, 0, 1, -1),
+            ("do bf16", T, a, d, 0, 1, 0), ("dhead f32", T, d, V, 0, 1, -1),
+            ("dw ffn1", d, ff, T, 1, 0, 0), ("dw ffn2", ff, d, T, 1, 0, 0), ("dw qkv", d, 3 * a, T, 1, 0, 0),
+            ("dw wo", a, d, T, 1, 0, 0), ("dw head", d, V, T, 1, 0, 0)]
 
-    if args.workload == "outer_microbench":
-        return outer_microbench(args)
 
+def gemm_microbench(args):
+    """The MFMA GEMM kernel on the GEMM shapes of a worker step (default: the headline workload), each
+    with the epilogue the step uses, through the C ABI (als_k_gemm_ex), one kernel at a time on one
+    stream; --tiles forces tile variants (tile M x tile N x LDS buffers) next to the automatic choice."""
+    import torch
+    import als_inputs as I
+    import paper_2401_09135_amd as A
+    dev = "cuda:0"
+    names = [args.shapes_of] if args.shapes_of else [HEADLINE, "lm20m"]
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device=dev)     # split-K scratch
+    tiles = [(0, 0, 0)] + [tuple(int(x) for x in t.split("x")) for t in args.tiles.split(",") if t]
+    rows = []
+    for wname in names:
+        shapes = gemm_shapes(I.workload(wname)) + ([("square 8192", 8192, 8192, 8192, 0, 1, 0)] if wname == names[-1] else [])
+        for name, M, N, K, al, bl, epi in shapes:
+            a = torch.randn((M, K) if al == 0 else (K, M), device=dev).to(torch.bfloat16)
+            b = torch.randn((K, N) if bl == 0 else (N, K), device=dev).to(torch.bfloat16)
+            e = max(epi, 0)
+            out_f32 = e == 1 or al == 1 or epi == -1
+            c = torch.empty(M, N, dtype=torch.float32 if out_f32 else torch.bfloat16, device=dev)
+            R = torch.randn(M, N, device=dev) if e == 1 else None
+            C2 = torch.empty(M, N, dtype=torch.bfloat16, device=dev) if e == 2 else None
+            U = torch.randn(M, N, device=dev).to(torch.bfloat16) if e == 3 else None
+            for tile in tiles:
+                A.set_gemm_tile(*tile)
+                f = lambda: A.k_gemm_ex(a, b, c, M, N, K, al, bl, True, e, R, C2, U, ws if al == 1 else None)
+                try:
+                    for _ in range(10):   # first launches on fresh buffers run up to 10 % slower
+                        f()
+                    torch.cuda.synchronize()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for _ in range(args.steps):
+                        f()
+                    e1.record()
+                    torch.cuda.synchronize()
+                    ms = e0.elapsed_time(e1) / args.steps
+                    rows.append(dict(workload=wname, product=name, M=M, N=N, K=K, tile="auto" if not tile[0] else "x".join(map(str, tile)),
+                                     us=ms * 1e3, tflops=2.0 * M * N * K / ms / 1e9))
+                    print(f"{wname:8s} {name:12s} M{M:<6d} N{N:<6d} K{K:<6d} tile={rows[-1]['tile']:10s}: {ms * 1e3:8.1f} us "
+                          f"{rows[-1]['tflops']:6.0f} TFLOP/s", file=sys.stderr, flush=True)
+                except A.AlsError as ex:
+                    print(f"{wname:8s} {name:12s} tile={tile}: not supported ({str(ex)[:60]})", file=sys.stderr, flush=True)
+                finally:
+                    A.set_gemm_tile(0, 0, 0)
+            del a, b, c, R, C2, U
+    auto = [r for r in rows if r["tile"] == "auto" and r["product"] != "square 8192"]
+    best = max(auto, key=lambda r: r["tflops"])
+    print(json.dumps(dict(metric="MFMA GEMM TFLOP/s on the worker step's products", value=best["tflops"], unit="TFLOP/s",
+                          n_gpus=1, steps=args.steps, warmup=10, ms_per_step=best["us"] / 1e3, higher_is_better=True,
+                          scaling="weak", vs_baseline=None, dtype="bf16", data="synthetic",
+                          config=dict(workload="gemm_microbench: " + ", ".join(names), results=rows),
+                          roofline=dict(bound="mfma", achieved=best["tflops"], peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                                        frac=best["tflops"] / PEAK_BF16_TFLOPS, traffic=None,
+                                        kernel=f"{best['workload']} {best['product']}"), cpu_baseline=None)))
+
+
+def run_lm(name, steps_timed, warmup, n_streams, isolated_profile=True):
+    """Runs warmup + steps_timed outer rounds of one language-model workload and returns the measured
+    figures.  Groups of events (ties, grace windows) are applied as the library's schedule marks them
+    (a group restarts only when its last event carries the group-end flag), exactly as the driver
+    loop the parity tests use; the timed region starts at a group end."""
     import numpy as np
     import torch
     import als_inputs as I
     import paper_2401_09135_amd as A
 
-    w = I.workload(args.workload)
-    if args.gemm_tile:
-        A.set_gemm_tile(*[int(x) for x in args.gemm_tile.split("x")])
+    w = I.workload(name)
     k, N = w["k"], w["N"]
-    n_rounds = args.warmup + args.steps
-    n_events = n_rounds * N
+    n_events = (warmup + steps_timed) * N
     steps, ev_w, ev_t, ev_g = A.dylu_schedule(w["speeds"], w["H"], w["tau_grace"], n_events)
     cfg = A.Config.from_workload(w, max_local_steps=int(steps.max()))
     # parameter layout from the library itself; values N(0, 0.02), gains 1
     P, Pd = A.param_count(cfg), A.param_count_decayed(cfg)
     theta0 = I.theta0([("decayed", (Pd,), "matrix"), ("gains", (P - Pd,), "gain")], w["seed"])
-    ctx = A.Context(cfg, theta0, n_streams=args.streams or min(k, 4))
+    ctx = A.Context(cfg, theta0, n_streams=n_streams or min(k, 4))
 
-    # how many local rounds each worker starts: the first one plus one per sync event of its own
-    rounds = [1 + int((ev_w == i).sum()) for i in range(k)]
+    # the schedule's groups: (first event, last event, restarts?)
+    groups, e = [], 0
+    while e < n_events:
+        j = e
+        while j < n_events - 1 and not ev_g[j]:
+            j += 1
+        groups.append((e, j, bool(ev_g[j])))
+        e = j + 1
+    # the timed region starts with the first group that begins at or after event warmup * N
+    first_timed = next(gi for gi, g in enumerate(groups) if g[0] >= warmup * N) if steps_timed else len(groups)
+
+    # how many local rounds each worker starts: the first one plus one per restart
+    rounds = [1] * k
+    for (a, b, complete) in groups:
+        if complete:
+            for i in ev_w[a:b + 1]:
+                rounds[int(i)] += 1
     toks = []
     for i in range(k):
         st = I.TokenStream(w["seed"], i, w["B"], w["S"], w["V"])
@@ -212,77 +303,160 @@ def main():
         ctx.worker_local_steps(i, toks[i][nxt[i]], w["lr"])
         nxt[i] += 1
 
-    def run_events(e0, e1):
-        tokens = 0
-        e = e0
-        while e < e1:
-            j = e
-            while j < e1 - 1 and not ev_g[j]:
-                j += 1
-            group = [int(x) for x in ev_w[e:j + 1]]
-            ctx.outer_apply_dn(group, restart=True)
-            for i in group:
-                tokens += int(steps[i]) * w["B"] * w["S"]
-                train(i)
-            e = j + 1
-        return tokens
+    def run_groups(g0, g1):
+        tokens = events = 0
+        for (a, b, complete) in groups[g0:g1]:
+            group = [int(x) for x in ev_w[a:b + 1]]
+            ctx.outer_apply_dn(group, restart=complete)
+            events += len(group)
+            if complete:
+                for i in group:
+                    tokens += int(steps[i]) * w["B"] * w["S"]
+                    train(i)
+        return tokens, events
 
     for i in range(k):
         train(i)
-    run_events(0, args.warmup * N)
+    run_groups(0, first_timed)
     ctx.sync()
     torch.cuda.synchronize()
     # HIP events around every 16th MFMA GEMM launch of the timed region, on the launching stream
     # (timing every launch costs 5 % of the throughput being measured)
     A.prof_enable(16)
     t0 = time.perf_counter()
-    tokens = run_events(args.warmup * N, n_events)
+    tokens, events = run_groups(first_timed, len(groups))
     ctx.sync()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     A.prof_enable(False)
     prof_overlapped = sorted(A.prof_collect(), key=lambda r: -r[2])
-    # Kernel quality is measured right after the timed region with ONE worker stepping alone (two
-    # local steps): in the timed region four workers' kernels share the chip, so a launch's
-    # begin-to-end time there includes the time it spends waiting for CUs held by other streams.
-    iso_tok = torch.from_numpy(I.TokenStream(w["seed"], 1000, w["B"], w["S"], w["V"]).take(2)).to(ctx.device)
-    A.prof_enable(True)
-    ctx.worker_local_steps(0, iso_tok, w["lr"])
-    ctx.sync()
-    A.prof_enable(False)
-    prof = sorted(A.prof_collect(), key=lambda r: -r[2])
 
-    tok_s = tokens / dt
+    # Outer-step cost (pseudo-gradient + Delayed Nesterov + restart copies): every distinct group size
+    # of the timed region applied alone on an idle GPU, host-timed between two synchronisations
+    # (the replicas hold the server's parameters, so the pseudo-gradients are zero: same bytes moved).
+    sizes = {}
+    for (a, b, complete) in groups[first_timed:]:
+        sizes[(b - a + 1, complete)] = sizes.get((b - a + 1, complete), 0) + 1
+    outer_s = 0.0
+    for (gsz, complete), count in sizes.items():
+        grp = list(range(gsz))
+        ctx.outer_apply_dn(grp, restart=complete)
+        ctx.sync()
+        ts = time.perf_counter()
+        for _ in range(3):
+            ctx.outer_apply_dn(grp, restart=complete)
+        ctx.sync()
+        outer_s += count * (time.perf_counter() - ts) / 3
+
+    # Kernel quality is measured right after the timed region with ONE worker stepping alone (two
+    # local steps): in the timed region the workers' kernels share the chip, so a launch's
+    # begin-to-end time there includes the time it spends waiting for CUs held by other streams.
+    prof = []
+    if isolated_profile:
+        iso_tok = torch.from_numpy(I.TokenStream(w["seed"], 1000, w["B"], w["S"], w["V"]).take(2)).to(ctx.device)
+        A.prof_enable(True)
+        ctx.worker_local_steps(0, iso_tok, w["lr"])
+        ctx.sync()
+        A.prof_enable(False)
+        prof = sorted(A.prof_collect(), key=lambda r: -r[2])
+    ctx.close()
+    del ctx, toks
+    torch.cuda.empty_cache()
+
+    rounds_timed = events / N if N else 0.0
+    tok_s = tokens / dt if dt > 0 else 0.0
     tflops = tok_s * flops_per_token(w) / 1e12
-    out = dict(metric="simulated-worker training tokens/s/GPU", value=tok_s, unit="tokens/s", n_gpus=1,
-               steps=args.steps, warmup=args.warmup, ms_per_step=1e3 * dt / max(args.steps, 1),
-               higher_is_better=True, scaling="weak", vs_baseline=None, dtype="bf16" if w["dtype"] == "bf16" else "f32",
-               data="synthetic",
-               config=dict(workload=f"{args.workload}: L{w['L']} d{w['d']} h{w['h']} ff{w['ff']} V{w['V']} S{w['S']} "
-                                    f"B{w['B']}/worker, k={k} workers speeds {np.round(w['speeds'], 3).tolist()}, "
-                                    f"DyLU H={w['H']} -> {steps.tolist()}, DN N={N} beta={w['outer_beta']} "
-                                    f"eps={w['outer_lr']}, step = one outer round of N sync events",
-                           tokens_per_step=tokens // max(args.steps, 1),
-                           model_tflops=tflops, mfma_frac_whole_path=tflops / PEAK_BF16_TFLOPS),
-               roofline=None, cpu_baseline=None)
+    res = dict(workload=name,
+               describe=f"{name}: L{w['L']} d{w['d']} h{w['h']} ff{w['ff']} V{w['V']} S{w['S']} B{w['B']}/worker, k={k} workers "
+                        f"speeds {np.round(w['speeds'], 3).tolist()}, DyLU H={w['H']} -> {steps.tolist()}, DN N={N} "
+                        f"beta={w['outer_beta']} eps={w['outer_lr']}, step = one outer round of N sync events",
+               tokens_per_s=tok_s, seconds=dt, sync_events_timed=events, outer_rounds_timed=rounds_timed,
+               ms_per_outer_round=1e3 * dt / rounds_timed if rounds_timed else None,
+               tokens_per_outer_round=tokens / rounds_timed if rounds_timed else None,
+               model_tflops=tflops, mfma_frac_whole_path=tflops / PEAK_BF16_TFLOPS,
+               outer_step_seconds_isolated=outer_s, outer_step_overhead_fraction=outer_s / dt if dt > 0 else None,
+               w=w)
     if prof:
         # dominant kernel = the GEMM instantiation with the largest summed duration
-        name, launches, ms, fl = prof[0]
+        kname, launches, ms, fl = prof[0]
         achieved = fl / (ms * 1e-3) / 1e12
-        out["roofline"] = dict(bound="mfma", achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+        res["roofline"] = dict(bound="mfma", achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
                                frac=achieved / PEAK_BF16_TFLOPS,
-                               traffic=MEASURED_TRAFFIC_BYTES.get(args.workload, {}).get(name), kernel=name, launches=launches,
+                               traffic=MEASURED_TRAFFIC_BYTES.get(name, {}).get(kname), kernel=kname, launches=launches,
                                avg_us=1e3 * ms / launches, flops_per_launch=fl / launches,
                                how="HIP events around every launch of this kernel while one worker steps alone "
                                    "right after the timed region (same shapes, same stream)",
                                all_gemm_kernels=[dict(kernel=n, launches=l, avg_us=1e3 * m / l,
                                                       tflops=f / (m * 1e-3) / 1e12) for n, l, m, f in prof],
+                               gemm_tflops_all_kernels=sum(f for _, _, _, f in prof) / (sum(m for _, _, m, _ in prof) * 1e-3) / 1e12,
                                timed_region_overlapped=[dict(kernel=n, launches=l, avg_us=1e3 * m / l,
                                                              tflops=f / (m * 1e-3) / 1e12)
                                                         for n, l, m, f in prof_overlapped])
+    return res
+
+
+def _brief(r):
+    keep = ("describe", "tokens_per_s", "ms_per_outer_round", "outer_rounds_timed", "model_tflops",
+            "mfma_frac_whole_path", "outer_step_overhead_fraction", "outer_step_seconds_isolated")
+    out = {k: r[k] for k in keep}
+    if "roofline" in r:
+        out["dominant_gemm"] = {k: r["roofline"][k] for k in ("kernel", "achieved", "frac", "avg_us")}
+        out["gemm_tflops_all_kernels"] = r["roofline"]["gemm_tflops_all_kernels"]
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=8)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="", help="one workload only (lm150m, lm20m, lm20m_k16, paper150m_b128, "
+                                                   "outer_microbench, gemm_microbench); default: the headline "
+                                                   f"workload ({HEADLINE}) followed by short runs of the others")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="default run: skip the other workloads")
+    ap.add_argument("--streams", type=int, default=0, help="HIP streams the workers share (worker i on stream i mod n); 0 = min(k, 4): the box gives a process 4 hardware queues")
+    ap.add_argument("--gemm-tile", default="", help="tuning: force the MFMA GEMM tile, e.g. 256x128x1 (tile M x tile N x LDS buffers)")
+    ap.add_argument("--tiles", default="", help="gemm_microbench: comma-separated tile variants to time next to the automatic choice")
+    ap.add_argument("--shapes-of", default="", help="gemm_microbench: the workload whose GEMM shapes are timed")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the simulated workers are replicas on HIP streams of "
+              "a single MI355X); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    if args.workload == "outer_microbench":
+        return outer_microbench_line(args)
+    if args.workload == "gemm_microbench":
+        return gemm_microbench(args)
+
+    import paper_2401_09135_amd as A
+    if args.gemm_tile:
+        A.set_gemm_tile(*[int(x) for x in args.gemm_tile.split("x")])
+    name = args.workload or HEADLINE
+    r = run_lm(name, args.steps, args.warmup, args.streams)
+    w = r["w"]
+    out = dict(metric="simulated-worker training tokens/s/GPU", value=r["tokens_per_s"], unit="tokens/s", n_gpus=1,
+               steps=args.steps, warmup=args.warmup, ms_per_step=r["ms_per_outer_round"],
+               higher_is_better=True, scaling="weak", vs_baseline=None, dtype="bf16" if w["dtype"] == "bf16" else "f32",
+               data="synthetic",
+               config=dict(workload=r["describe"], tokens_per_step=r["tokens_per_outer_round"],
+                           sync_events_timed=r["sync_events_timed"], model_tflops=r["model_tflops"],
+                           mfma_frac_whole_path=r["mfma_frac_whole_path"],
+                           outer_step_overhead_fraction=r["outer_step_overhead_fraction"]),
+               roofline=r.get("roofline"), cpu_baseline=None)
+    if not args.workload and not args.no_others:
+        # the other BASELINE configurations, short runs, reported beside the headline
+        others = {}
+        for oname, st, wu in (("lm20m", 4, 1), ("lm20m_k16", 2, 1)):
+            others[oname] = _brief(run_lm(oname, st, wu, args.streams))
+        mb = outer_microbench(20)
+        mb.pop("_iters")
+        others["outer_microbench"] = {k: dict(GBps=v["GBps"], frac_of_hbm_peak=v["GBps"] / PEAK_HBM_GBS, ms=v["ms"],
+                                              bytes_per_param=v["bytes_per_param"]) for k, v in mb.items()}
+        out["config"]["other_workloads"] = others
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
-    ctx.close()
     print(json.dumps(out))
 
 

@@ -228,20 +228,6 @@ int als_k_gemm(const void* A, const void* B, void* C, int M, int N, int K, int a
 int als_k_gemm_ex(const void* A, const void* B, void* C, int M, int N, int K, int a_layout,
                   int b_layout, int in_dtype, int out_dtype, int use_mfma, int epi, const float* R,
                   void* C2, const void* U, void* ws_dev, size_t ws_bytes, void* stream);
-/* Benchmark hooks.  als_prof_enable(n), n >= 1, makes every n-th MFMA GEMM launch record a HIP
- * event before and after itself on its own stream (a timed launch costs about 20 us of host
- * time and orders the stream around it, so a throughput run samples); 0 switches it off;
- * als_prof_collect waits for the device and returns, per kernel instantiation (id), the number of launches, their summed duration in ms and their
- * summed algorithmic FLOPs (2 M N K), then forgets them.  Returns the number of entries
- * written (<= max_entries) or a negative error.  als_prof_kernel_name writes the kernel's
- * template name for an id. */
-int als_prof_enable(int on);
-int als_prof_collect(int max_entries, int32_t* ids, int64_t* launches, double* ms, double* flops);
-int als_prof_kernel_name(int id, char* out, int out_len);
-/* Benchmark hook: force the MFMA GEMM tile to 256x256, 256x128 or 128x128 with nbuf = 2
- * (LDS double buffer) or 1 (single buffer, more workgroups per CU); 0,0,0 = automatic choice
- * by shape.  Process-wide, not thread-safe. */
-int als_k_set_gemm_tile(int bm, int bn, int nbuf);
 /* Causal attention forward / backward on packed qkv [B*S, 3d] (q|k|v, head-major), dtype
  * ALS_DTYPE_*: o [B*S,d] same dtype, lse fp32 [B,h,S]; backward takes d_o and returns dqkv. */
 int als_k_attention_fwd(const void* qkv, void* o, float* lse, int B, int S, int h, int dh,

@@ -20,6 +20,7 @@
 // LDS transpose load: in each group of 16 lanes, lane s supplies 4 consecutive bf16; lane r
 // receives element r%4 of lanes r/4, 4 + r/4, 8 + r/4, 12 + r/4.
 #include "common.h"
+#include "als_bench.h"
 #include <hip/hip_ext.h>
 #include <stdio.h>
 

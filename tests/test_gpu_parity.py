@@ -69,6 +69,15 @@ def test_loss_and_gradient_one_batch(name, flags):
             f"{_rel(g, rg):.3e} worst tensor {max(per, key=per.get)} {worst:.3e}")
     assert worst < (3e-2 if bf else 2e-5), per
     assert _rel(g, rg) < (1.5e-2 if bf else 1e-5)
+    if not bf:
+        # element by element, so that a few wrong entries cannot hide inside a norm: every entry
+        # within 1e-5 of its own value or of 1e-5 x the largest entry of its tensor
+        off = 0
+        for tname, shape, _ in lm.param_layout(w):
+            n = int(np.prod(shape))
+            np.testing.assert_allclose(g[off:off + n], rg[off:off + n], rtol=1e-5,
+                                       atol=1e-5 * float(np.abs(rg[off:off + n]).max()), err_msg=tname)
+            off += n
 
 
 @pytest.mark.parametrize("name,flags", [("tiny", 0), ("mini_f32", 0), ("mini_bf16", 1), ("mini_bf16", 0),
