@@ -228,6 +228,21 @@ int als_k_gemm(const void* A, const void* B, void* C, int M, int N, int K, int a
 int als_k_gemm_ex(const void* A, const void* B, void* C, int M, int N, int K, int a_layout,
                   int b_layout, int in_dtype, int out_dtype, int use_mfma, int epi, const float* R,
                   void* C2, const void* U, void* ws_dev, size_t ws_bytes, void* stream);
+/* For callers that cannot allocate device memory and have no workspace to lend (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): als_k_gemm on the MFMA
+ * path (bf16 operands, M, N multiples of 128, K of 64) with the split-K partials of the
+ * weight-gradient layout (a_layout 1, b_layout 0) kept in a file-scope device array of
+ * ALS_STATIC_WS_BYTES that every GPU the library runs on holds until the process ends.  Calls no
+ * hipMalloc / hipFree or any allocating routine.  Results equal als_k_gemm with a workspace of
+ * ALS_STATIC_WS_BYTES, bit for bit.  Errors (ALS_ERR_INVALID): null pointers, shapes the MFMA
+ * kernel does not take, M * N * 8 > ALS_STATIC_WS_BYTES (two fp32 partials must fit).  All calls
+ * on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams or
+ * threads) race on it; calls on one stream are ordered.  Nothing in the array has to start at
+ * zero: every partial is written in full before it is read.  The current device must be the
+ * stream's device. */
+#define ALS_STATIC_WS_BYTES ((size_t)64 << 20)
+int als_k_gemm_static_ws(const void* A, const void* B, void* C, int M, int N, int K, int a_layout,
+                         int b_layout, int out_dtype, void* stream);
 /* Causal attention forward / backward on packed qkv [B*S, 3d] (q|k|v, head-major), dtype
  * ALS_DTYPE_*: o [B*S,d] same dtype, lse fp32 [B,h,S]; backward takes d_o and returns dqkv. */
 int als_k_attention_fwd(const void* qkv, void* o, float* lse, int B, int S, int h, int dh,

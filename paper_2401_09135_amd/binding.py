@@ -331,6 +331,16 @@ def k_gemm(A, B, C_out, M, N, K, a_layout=0, b_layout=0, use_mfma=False, ws=None
                           ws.numel() * ws.element_size() if ws is not None else 0, _stream_handle(stream)))
 
 
+STATIC_WS_BYTES = 64 << 20
+lib.als_k_gemm_static_ws.argtypes = [_P, _P, _P, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, _P]
+
+
+def k_gemm_static_ws(A, B, C_out, M, N, K, a_layout=1, b_layout=0, stream=None):
+    """als_k_gemm on the MFMA path with the split-K partials in the library's static device array."""
+    _check(lib.als_k_gemm_static_ws(A.data_ptr(), B.data_ptr(), C_out.data_ptr(), M, N, K, a_layout, b_layout,
+                                    _dt(C_out), _stream_handle(stream)))
+
+
 lib.als_k_gemm_ex.argtypes = [_P, _P, _P, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                               _P, _P, _P, _P, C.c_size_t, _P]
 

@@ -5,6 +5,7 @@
 #include "common.h"
 #include <math.h>
 #include <string.h>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -562,6 +563,56 @@ extern "C" int als_k_gemm(const void* A, const void* B, void* C, int M, int N, i
     return gemm_mfma(g, (hipStream_t)stream);
   }
   return gemm_generic(g, (hipStream_t)stream);
+}
+
+// ---- the entry point that allocates nothing ---------------------------------------------------
+// Split-K partials of the stand-alone weight-gradient product live in this file-scope device
+// array instead of a caller workspace.  Every GPU the library runs on holds its own copy of the
+// array until the process ends; the host only ever uses the address hipGetSymbolAddress() returns
+// for the current device (the array's name in host code is a stand-in, not a device address).
+static __device__ __align__(256) unsigned char scratch[ALS_STATIC_WS_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices];   // per device, filled at the first call on that device
+
+int scratch_for_current_device(void** out) {
+  int dev = -1;
+  ALS_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return als::set_error(ALS_ERR_INVALID, "device index %d out of range", dev);
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    ALS_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return als::set_error(ALS_ERR_HIP, "hipGetSymbolAddress returned a null address");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return ALS_OK;
+}
+}  // namespace
+
+extern "C" int als_k_gemm_static_ws(const void* A, const void* B, void* C, int M, int N, int K, int a_layout,
+                                    int b_layout, int out_dtype, void* stream) {
+  if (!A || !B || !C) return set_error(ALS_ERR_INVALID, "null argument");
+  if (M <= 0 || N <= 0 || K <= 0) return set_error(ALS_ERR_INVALID, "M, N, K must be positive");
+  // two fp32 partials of the product must fit, so that the split along K has room to happen
+  if ((uint64_t)M * (uint64_t)N * sizeof(float) * 2 > (uint64_t)ALS_STATIC_WS_BYTES)
+    return set_error(ALS_ERR_INVALID, "als_k_gemm_static_ws: M x N = %d x %d exceeds the static workspace "
+                     "(2 fp32 partials must fit %zu bytes, i.e. M*N <= %zu)", M, N, (size_t)ALS_STATIC_WS_BYTES,
+                     (size_t)ALS_STATIC_WS_BYTES / 8);
+  GemmDesc g;
+  memset(&g, 0, sizeof g);
+  g.A = A; g.B = B; g.C = C; g.M = M; g.N = N; g.K = K; g.a_layout = a_layout; g.b_layout = b_layout;
+  g.lda = a_layout == 0 ? K : M; g.ldb = b_layout == 0 ? N : K; g.ldc = N;
+  g.in_bf16 = 1; g.c_bf16 = out_dtype == ALS_DTYPE_BF16; g.epi = EPI_STORE;
+  if (!gemm_mfma_supported(g)) return set_error(ALS_ERR_INVALID, "shape/dtype not supported by the MFMA GEMM");
+  void* ws = nullptr;
+  int rc = scratch_for_current_device(&ws);
+  if (rc) return rc;
+  g.ws = (float*)ws; g.ws_bytes = ALS_STATIC_WS_BYTES;
+  return gemm_mfma(g, (hipStream_t)stream);
 }
 
 extern "C" int als_k_gemm_ex(const void* A, const void* B, void* C, int M, int N, int K, int a_layout,
