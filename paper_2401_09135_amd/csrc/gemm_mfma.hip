@@ -107,6 +107,111 @@ struct MfmaArgs {
   int64_t split_stride;  // elements between split partials (split-K only)
 };
 
+// Epilogue of one wavefront's WM x WN sub-tile (TM x TN accumulator blocks of 32 x 32) whose top
+// left element is (row0, col0) of C.  The sub-tile is staged through LDS, 32 rows at a time (fp32,
+// row pitch padded by 16 bytes), and read back so that the lanes of one store instruction cover
+// whole row segments, 16 bytes per lane: every global access of the epilogue (residual and
+// saved-derivative reads, outputs) is then fully coalesced.  (Storing straight from the
+// accumulator layout gives 8- or 16-byte pieces in 32 different rows per instruction; measured
+// 8 % slower on the whole step.)
+template <int TM, int TN, int WN, int EPI, typename TO>
+struct WaveEpilogue {
+  static constexpr int PITCH = WN * 4 + 16;  // rows 4 banks apart: 16-byte accesses of 16 rows, or of two row halves, never collide
+  static constexpr int CPL = sizeof(TO) == 2 ? 8 : 4;  // consecutive columns per lane
+  static constexpr int LPR = WN / CPL;                 // lanes per row
+  static constexpr int RPP = 64 / LPR;                 // rows per pass
+  static constexpr int NPASS = 32 / RPP;
+  // The epilogue's global READS (residual rows, saved derivative) are issued together, ahead of
+  // the staging and the stores: loads and stores complete out of order with respect to each
+  // other, so a load issued after a store can only be waited for with "everything done", and a
+  // load per pass would expose one full memory latency per pass.  All of the sub-tile at once
+  // when that fits in 64 registers, else one 32-row block at a time.
+  static constexpr bool HAS_AUX = EPI == EPI_RESID || EPI == EPI_DGELU;
+  static constexpr bool AUX_ALL = TM * NPASS * 4 <= 64;
+  u32x4 aux[HAS_AUX ? TM : 1][HAS_AUX ? NPASS : 1];
+  const MfmaArgs& g;
+  const int lane, row0, col0;
+  __device__ __forceinline__ WaveEpilogue(const MfmaArgs& g_, int lane_, int row0_, int col0_)
+      : g(g_), lane(lane_), row0(row0_), col0(col0_) {}
+  __device__ __forceinline__ void load_aux(int i) {
+#pragma unroll
+    for (int pass = 0; pass < NPASS; pass++) {
+      const int row = row0 + i * 32 + pass * RPP + lane / LPR;
+      const int col = col0 + (lane % LPR) * CPL;
+      if (EPI == EPI_RESID) aux[HAS_AUX ? i : 0][HAS_AUX ? pass : 0] = *reinterpret_cast<const u32x4*>(g.R + (int64_t)row * g.ldr + col);
+      else aux[HAS_AUX ? i : 0][HAS_AUX ? pass : 0] = *reinterpret_cast<const u32x4*>(g.U + (int64_t)row * g.ldc + col);
+    }
+  }
+  __device__ __forceinline__ void preload() {
+    if (HAS_AUX && AUX_ALL) {
+#pragma unroll
+      for (int i = 0; i < TM; i++) load_aux(i);
+    }
+  }
+  // stg: this wavefront's 32 x PITCH bytes of LDS; every wavefront that could still read operand
+  // tiles there must be done with them
+  __device__ __forceinline__ void run(f32x16 (&acc)[TM][TN], char* stg, TO* C) {
+#pragma unroll
+    for (int i = 0; i < TM; i++) {
+      if (HAS_AUX && !AUX_ALL) load_aux(i);
+#pragma unroll
+      for (int j = 0; j < TN; j++)
+#pragma unroll
+        for (int gq = 0; gq < 4; gq++) {
+          f32x4 x = {acc[i][j][4 * gq], acc[i][j][4 * gq + 1], acc[i][j][4 * gq + 2], acc[i][j][4 * gq + 3]};
+          *reinterpret_cast<f32x4*>(stg + (lane & 31) * PITCH + (j * 32 + 8 * gq + 4 * (lane >> 5)) * 4) = x;
+        }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // wave-local staging: its own writes have landed
+#pragma unroll
+      for (int pass = 0; pass < NPASS; pass++) {
+        const int rr = pass * RPP + lane / LPR;
+        const int cc = (lane % LPR) * CPL;
+        const int row = row0 + i * 32 + rr;
+        const int col = col0 + cc;
+        const int64_t ci = (int64_t)row * g.ldc + col;
+        float x[CPL];
+#pragma unroll
+        for (int q = 0; q < CPL / 4; q++) {
+          f32x4 v = *reinterpret_cast<const f32x4*>(stg + rr * PITCH + (cc + 4 * q) * 4);
+          x[4 * q] = v[0]; x[4 * q + 1] = v[1]; x[4 * q + 2] = v[2]; x[4 * q + 3] = v[3];
+        }
+        if (EPI == EPI_RESID) {
+          f32x4 r = __builtin_bit_cast(f32x4, aux[HAS_AUX ? i : 0][HAS_AUX ? pass : 0]);
+#pragma unroll
+          for (int e = 0; e < 4; e++) x[e] += r[e];
+        }
+        if (EPI == EPI_DGELU) {  // U holds gelu'(pre-activation), saved by the forward pass
+          bf16x8 u = __builtin_bit_cast(bf16x8, aux[HAS_AUX ? i : 0][HAS_AUX ? pass : 0]);
+#pragma unroll
+          for (int e = 0; e < CPL; e++) x[e] *= (float)u[e & 7];
+        }
+        if (sizeof(TO) == 4) {
+          f32x4 o = {x[0], x[1], x[2], x[3]};
+          *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(C) + ci) = o;
+        } else {
+          bf16x8 o;
+          if (EPI == EPI_GELU) {  // C <- gelu'(acc), C2 <- gelu(acc)
+            bf16x8 o2;
+#pragma unroll
+            for (int e = 0; e < CPL; e++) {
+              float val, grad;
+              gelu_both(x[e], val, grad);
+              o[e & 7] = (bf16)grad;
+              o2[e & 7] = (bf16)val;
+            }
+            *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16*>(g.C2) + ci) = o2;
+          } else {
+#pragma unroll
+            for (int e = 0; e < CPL; e++) o[e & 7] = (bf16)x[e];
+          }
+          *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16*>(C) + ci) = o;
+        }
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // reads done before the next block overwrites
+    }
+  }
+};
+
 // NBUF = 2: LDS double buffer, one barrier per K slice, one workgroup per CU for the large
 // tiles.  NBUF = 1: single LDS buffer, two barriers per slice, but half the LDS so that OCC
 // workgroups share a CU and one's epilogue and barrier stalls hide behind another's MFMAs.
@@ -279,101 +384,216 @@ __global__ __launch_bounds__(64 * tile_waves(BM, BN), OCC) void gemm_mfma_kernel
     }
   }
 
-  // Epilogue.  Each wavefront stages its sub-tile through LDS, 32 rows at a time (fp32, row
-  // pitch padded by 16 bytes), and reads it back so that the lanes of one store instruction
-  // cover whole row segments, 16 bytes per lane: every global access of the epilogue (residual
-  // and saved-derivative reads, outputs) is then fully coalesced.  (Storing straight from the
-  // accumulator layout gives 8- or 16-byte pieces in 32 different rows per instruction;
-  // measured 8 % slower on the whole step.)
+  // Epilogue (WaveEpilogue above): each wavefront stages its sub-tile through the operand buffers.
   TO* C = reinterpret_cast<TO*>(g.C);
   if (SPLIT) C += (int64_t)zsplit * g.split_stride;
-  constexpr int PITCH = WN * 4 + 16;  // rows 4 banks apart: 16-byte accesses of 16 rows, or of two row halves, never collide
-  static_assert(NW * 32 * PITCH <= TL::LDS_BYTES, "epilogue staging must fit the operand buffers");
-  char* stg = smem + wave * (32 * PITCH);
-  constexpr int CPL = sizeof(TO) == 2 ? 8 : 4;  // consecutive columns per lane
-  constexpr int LPR = WN / CPL;                 // lanes per row
-  constexpr int RPP = 64 / LPR;                 // rows per pass
-  constexpr int NPASS = 32 / RPP;
-  // The epilogue's global READS (residual rows, saved derivative) are issued together, ahead of
-  // the staging and the stores: loads and stores complete out of order with respect to each
-  // other, so a load issued after a store can only be waited for with "everything done", and a
-  // load per pass would expose one full memory latency per pass.  All of the sub-tile at once
-  // when that fits in 64 registers, else one 32-row block at a time.
-  constexpr bool HAS_AUX = EPI == EPI_RESID || EPI == EPI_DGELU;
-  constexpr bool AUX_ALL = TM * NPASS * 4 <= 64;
-  u32x4 aux[HAS_AUX ? TM : 1][HAS_AUX ? NPASS : 1];
-  auto load_aux = [&](int i) {
-#pragma unroll
-    for (int pass = 0; pass < NPASS; pass++) {
-      const int row = m0 + wm * WM + i * 32 + pass * RPP + lane / LPR;
-      const int col = n0 + wn * WN + (lane % LPR) * CPL;
-      if (EPI == EPI_RESID) aux[i][pass] = *reinterpret_cast<const u32x4*>(g.R + (int64_t)row * g.ldr + col);
-      else aux[i][pass] = *reinterpret_cast<const u32x4*>(g.U + (int64_t)row * g.ldc + col);
-    }
-  };
-  if (HAS_AUX && AUX_ALL) {
-#pragma unroll
-    for (int i = 0; i < TM; i++) load_aux(i);
-  }
+  typedef WaveEpilogue<TM, TN, WN, EPI, TO> EP;
+  static_assert(NW * 32 * EP::PITCH <= TL::LDS_BYTES, "epilogue staging must fit the operand buffers");
+  EP ep(g, lane, m0 + wm * WM, n0 + wn * WN);
+  ep.preload();
   __syncthreads();  // every wave is done with the operand tiles
+  ep.run(acc, smem + wave * (32 * EP::PITCH), C);
+}
+
+// ---- 256 x 256 tile, two wavefront groups in alternating phases ("ping-pong") ----------------
+// The vector-memory path feeds a CU about 40 bytes per clock; a 256 x 128 tile at the full MFMA
+// rate needs 47, a 256 x 256 tile 32: the larger tile is what the memory path allows.  It leaves
+// room for ONE workgroup per CU, so the overlap that two independent workgroups give the smaller
+// tiles is built into the workgroup here: 8 wavefronts in two groups of four (group g owns columns
+// 128 g .. 128 g + 127 of the tile, each wavefront 128 x 64 of them), every SIMD hosting one
+// wavefront of each group.  A group alternates between a MEMORY phase (fragment reads of one
+// 32-wide half of the K slice from LDS into registers, LDS stores of its share of the next slice,
+// global loads of the slice after that) and a COMPUTE phase (16 MFMAs on those registers, nothing
+// else).  The groups run one phase apart, separated by workgroup barriers, so each SIMD's matrix
+// pipe always sees exactly one wavefront issuing back-to-back MFMAs while the other wavefront's
+// LDS traffic, address arithmetic and waits hide behind them.
+//
+// Phases (kt = K slice, h = its half; p counts workgroup barriers):
+//   group 0: M(kt,h) at p = 4 kt + 2 h, C(kt,h) at p + 1; group 1 the same one phase later.
+//   LDS double buffer: slice kt lives in buffer kt & 1.  Slice kt+1 is written into the other
+//   buffer during the M phases of slice kt (A chunks in M(kt,0), B chunks in M(kt,1)): the last
+//   reads of its previous content (slice kt-1) ended at p = 4 kt - 1 and its first read is at
+//   p = 4 kt + 4.  The global loads of a chunk are issued right after the chunk's registers were
+//   stored, a whole slice (four phases) before they are needed.
+// Rows / columns beyond M / N (M, N multiples of 128, not of 256) are loaded from clamped
+// addresses, multiplied, and not stored: a wavefront's 128 x 64 sub-tile is wholly inside or outside.
+template <int AL, int BL, int EPI, typename TO, bool SPLIT>
+__global__ __launch_bounds__(512, 1) void gemm_pp_kernel(MfmaArgs g) {
+  constexpr int BM = 256, BN = 256;
+  typedef Tile<BM, BN, AL, BL, 2> TL;
+  static_assert(TL::NT == 512 && TL::A_CHUNKS == 4 && TL::B_CHUNKS == 4, "8 wavefronts, 4 + 4 chunks per thread");
+  constexpr int WM = 128, WN = 64, TM = 4, TN = 2;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int grp = wave >> 2, wm = (wave >> 1) & 1, wn = wave & 1;
+  const int ncol0 = grp * 128 + wn * WN;   // this wavefront's first column inside the tile
+
+  int ntiles = g.tiles_m * g.tiles_n;
+  int id = blockIdx.x, tile, zsplit = 0;
+  if (SPLIT) {
+    zsplit = id % g.nsplit;
+    tile = id / g.nsplit;
+  } else {
+    int per = ntiles / 8;
+    tile = (id < per * 8) ? (id % 8) * per + id / 8 : id;
+  }
+  // Tiles are numbered down column blocks 8 tiles wide, so that the 32 tiles an XCD works on at
+  // a time form a 4 x 8 patch sharing 4 A panels and 8 B panels in its L2 (a row of 32 tiles would
+  // share one A panel and stream 32 B panels through it).
+  int tm, tn;
+  {
+    constexpr int GN = 8;
+    const int span = GN * g.tiles_m, b = tile / span, r = tile - b * span;
+    const int width = g.tiles_n - b * GN < GN ? g.tiles_n - b * GN : GN;
+    tm = r / width;
+    tn = b * GN + r % width;
+  }
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int64_t kbase = (int64_t)zsplit * g.K;
+  const int nk = g.K / BK;
+
+  // global addressing: scalar tile origin + per-lane, per-chunk 32-bit byte offsets (rows / column
+  // runs beyond the matrix are clamped onto its last ones)
+  const char* Ag = reinterpret_cast<const char*>(AL == 0 ? g.A + (int64_t)m0 * g.lda + kbase : g.A + kbase * g.lda + m0);
+  const char* Bg = reinterpret_cast<const char*>(BL == 1 ? g.B + (int64_t)n0 * g.ldb + kbase : g.B + kbase * g.ldb + n0);
+  constexpr int A_CPR = AL == 0 ? 8 : BM / 8, B_CPR = BL == 1 ? 8 : BN / 8;
+  constexpr int A_RPC = TL::NT / A_CPR, B_RPC = TL::NT / B_CPR;
+  auto tile_row = [](int q) { return (q & ~15) | ((q & 15) >> 1) | ((q & 1) << 3); };
+  const int a_row = AL == 0 ? tile_row(tid / A_CPR) : tid / A_CPR;
+  const int b_row = BL == 1 ? tile_row(tid / B_CPR) : tid / B_CPR;
+  int a_goff[4], b_goff[4];
 #pragma unroll
-  for (int i = 0; i < TM; i++) {
-    if (HAS_AUX && !AUX_ALL) load_aux(i);
+  for (int i = 0; i < 4; i++) {
+    if (AL == 0) {
+      int r = a_row + i * A_RPC;
+      r = m0 + r < g.M ? r : g.M - 1 - m0;
+      a_goff[i] = (int)(((int64_t)r * g.lda + (tid % A_CPR) * 8) * 2);
+    } else {
+      int c = (tid % A_CPR) * 8;
+      c = m0 + c < g.M ? c : g.M - 8 - m0;
+      a_goff[i] = (int)(((int64_t)(a_row + i * A_RPC) * g.lda + c) * 2);
+    }
+    if (BL == 1) {
+      int r = b_row + i * B_RPC;
+      r = n0 + r < g.N ? r : g.N - 1 - n0;
+      b_goff[i] = (int)(((int64_t)r * g.ldb + (tid % B_CPR) * 8) * 2);
+    } else {
+      int c = (tid % B_CPR) * 8;
+      c = n0 + c < g.N ? c : g.N - 8 - n0;
+      b_goff[i] = (int)(((int64_t)(b_row + i * B_RPC) * g.ldb + c) * 2);
+    }
+  }
+  const int64_t a_step = AL == 0 ? BK * 2 : (int64_t)BK * g.lda * 2;
+  const int64_t b_step = BL == 1 ? BK * 2 : (int64_t)BK * g.ldb * 2;
+  const int a_soff = a_row * TL::A_STRIDE + (tid % A_CPR) * 16;
+  const int b_soff = b_row * TL::B_STRIDE + (tid % B_CPR) * 16;
+
+  u32x4 ra[4], rb[4];
+  auto load_a = [&](int kt) {
+    const char* ap = Ag + kt * a_step;
+#pragma unroll
+    for (int i = 0; i < 4; i++) ra[i] = *reinterpret_cast<const u32x4*>(ap + a_goff[i]);
+  };
+  auto load_b = [&](int kt) {
+    const char* bp = Bg + kt * b_step;
+#pragma unroll
+    for (int i = 0; i < 4; i++) rb[i] = *reinterpret_cast<const u32x4*>(bp + b_goff[i]);
+  };
+  auto store_a = [&](int buf) {
+    char* As = smem + buf * TL::STAGE;
+#pragma unroll
+    for (int i = 0; i < 4; i++) *reinterpret_cast<u32x4*>(As + a_soff + i * (A_RPC * TL::A_STRIDE)) = ra[i];
+  };
+  auto store_b = [&](int buf) {
+    char* Bs = smem + buf * TL::STAGE + TL::A_BYTES;
+#pragma unroll
+    for (int i = 0; i < 4; i++) *reinterpret_cast<u32x4*>(Bs + b_soff + i * (B_RPC * TL::B_STRIDE)) = rb[i];
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
 #pragma unroll
     for (int j = 0; j < TN; j++)
 #pragma unroll
-      for (int gq = 0; gq < 4; gq++) {
-        f32x4 x = {acc[i][j][4 * gq], acc[i][j][4 * gq + 1], acc[i][j][4 * gq + 2], acc[i][j][4 * gq + 3]};
-        *reinterpret_cast<f32x4*>(stg + (lane & 31) * PITCH + (j * 32 + 8 * gq + 4 * (lane >> 5)) * 4) = x;
+      for (int v = 0; v < 16; v++) acc[i][j][v] = 0.0f;
+
+  int a_off, b_off;
+  if (AL == 0) a_off = (wm * WM + (lane & 31)) * TL::A_STRIDE + (lane >> 5) * 16;
+  else a_off = ((lane >> 5) * 8 + ((lane & 15) >> 2)) * TL::A_STRIDE + (wm * WM + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;
+  if (BL == 1) b_off = (ncol0 + (lane & 31)) * TL::B_STRIDE + (lane >> 5) * 16;
+  else b_off = ((lane >> 5) * 8 + ((lane & 15) >> 2)) * TL::B_STRIDE + (ncol0 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;
+
+  bf16x8 af[2][TM], bfr[2][TN];   // fragments of one 32-wide half of a K slice
+  auto memory_phase = [&](int kt, int h) {
+    const char* As = smem + (kt & 1) * TL::STAGE;
+    const char* Bs = As + TL::A_BYTES;
+#pragma unroll
+    for (int s2 = 0; s2 < 2; s2++) {
+      const int kk = 2 * h + s2;
+#pragma unroll
+      for (int j = 0; j < TN; j++) {
+        if (BL == 1) bfr[s2][j] = lds_read_direct(Bs + b_off + j * 32 * TL::B_STRIDE + kk * 32);
+        else bfr[s2][j] = lds_read_tr(Bs + b_off + kk * 16 * TL::B_STRIDE + j * 64, TL::B_STRIDE);
       }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // wave-local staging: its own writes have landed
 #pragma unroll
-    for (int pass = 0; pass < NPASS; pass++) {
-      const int rr = pass * RPP + lane / LPR;
-      const int cc = (lane % LPR) * CPL;
-      const int row = m0 + wm * WM + i * 32 + rr;
-      const int col = n0 + wn * WN + cc;
-      const int64_t ci = (int64_t)row * g.ldc + col;
-      float x[CPL];
-#pragma unroll
-      for (int q = 0; q < CPL / 4; q++) {
-        f32x4 v = *reinterpret_cast<const f32x4*>(stg + rr * PITCH + (cc + 4 * q) * 4);
-        x[4 * q] = v[0]; x[4 * q + 1] = v[1]; x[4 * q + 2] = v[2]; x[4 * q + 3] = v[3];
-      }
-      if (EPI == EPI_RESID) {
-        f32x4 r = __builtin_bit_cast(f32x4, aux[HAS_AUX ? i : 0][HAS_AUX ? pass : 0]);
-#pragma unroll
-        for (int e = 0; e < 4; e++) x[e] += r[e];
-      }
-      if (EPI == EPI_DGELU) {  // U holds gelu'(pre-activation), saved by the forward pass
-        bf16x8 u = __builtin_bit_cast(bf16x8, aux[HAS_AUX ? i : 0][HAS_AUX ? pass : 0]);
-#pragma unroll
-        for (int e = 0; e < CPL; e++) x[e] *= (float)u[e & 7];
-      }
-      if (sizeof(TO) == 4) {
-        f32x4 o = {x[0], x[1], x[2], x[3]};
-        *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(C) + ci) = o;
-      } else {
-        bf16x8 o;
-        if (EPI == EPI_GELU) {  // C <- gelu'(acc), C2 <- gelu(acc)
-          bf16x8 o2;
-#pragma unroll
-          for (int e = 0; e < CPL; e++) {
-            float val, grad;
-            gelu_both(x[e], val, grad);
-            o[e & 7] = (bf16)grad;
-            o2[e & 7] = (bf16)val;
-          }
-          *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16*>(g.C2) + ci) = o2;
-        } else {
-#pragma unroll
-          for (int e = 0; e < CPL; e++) o[e & 7] = (bf16)x[e];
-        }
-        *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16*>(C) + ci) = o;
+      for (int i = 0; i < TM; i++) {
+        if (AL == 0) af[s2][i] = lds_read_direct(As + a_off + i * 32 * TL::A_STRIDE + kk * 32);
+        else af[s2][i] = lds_read_tr(As + a_off + kk * 16 * TL::A_STRIDE + i * 64, TL::A_STRIDE);
       }
     }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // reads done before the next block overwrites
+    if (kt + 1 < nk) {
+      if (h == 0) store_a((kt + 1) & 1); else store_b((kt + 1) & 1);
+    }
+    // unconditional (the last slices load the last slice again): with a fixed number of loads in
+    // flight the waits before the stores above count exactly, and leave the newer half in flight
+    const int kl = kt + 2 < nk ? kt + 2 : nk - 1;
+    if (h == 0) load_a(kl); else load_b(kl);
+  };
+  auto compute_phase = [&]() {
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+    for (int s2 = 0; s2 < 2; s2++)
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[s2][j], af[s2][i], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  // prologue: slice 0 into buffer 0, slice 1 into the registers
+  load_a(0);
+  load_b(0);
+  store_a(0);
+  store_b(0);
+  load_a(nk > 1 ? 1 : 0);
+  load_b(nk > 1 ? 1 : 0);
+  __syncthreads();
+  if (grp == 1) __builtin_amdgcn_s_barrier();   // group 1 runs one phase behind group 0
+  for (int kt = 0; kt < nk; kt++) {
+#pragma unroll
+    for (int h = 0; h < 2; h++) {
+      memory_phase(kt, h);
+      __syncthreads();   // LDS stores visible, fragments in registers
+      compute_phase();
+      // Both groups execute 4 nk barriers in all: group 1's would-be last one (after its last
+      // compute phase) guards nothing.  Group 0's last one is paired with the end of group 1's last
+      // memory phase: after it nobody reads operand tiles any more.
+      if (!(grp == 1 && kt == nk - 1 && h == 1)) __builtin_amdgcn_s_barrier();
+    }
   }
+
+  if (m0 + wm * WM >= g.M || n0 + ncol0 >= g.N) return;   // sub-tile outside the matrix
+  TO* C = reinterpret_cast<TO*>(g.C);
+  if (SPLIT) C += (int64_t)zsplit * g.split_stride;
+  typedef WaveEpilogue<TM, TN, WN, EPI, TO> EP;
+  static_assert(8 * 32 * EP::PITCH <= TL::LDS_BYTES, "epilogue staging must fit the operand buffers");
+  EP ep(g, lane, m0 + wm * WM, n0 + ncol0);
+  ep.preload();
+  ep.run(acc, smem + wave * (32 * EP::PITCH), C);
 }
 
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part,
@@ -432,6 +652,38 @@ int launch(const MfmaArgs& a, int nsplit, hipStream_t st) {
   return ALS_OK;
 }
 
+template <int AL, int BL, int EPI, typename TO, bool SPLIT>
+int launch_pp(const MfmaArgs& a, int nsplit, hipStream_t st) {
+  typedef Tile<256, 256, AL, BL, 2> TL;
+  auto kern = gemm_pp_kernel<AL, BL, EPI, TO, SPLIT>;
+  static bool attr_set = false;  // idempotent; a race only repeats the call
+  if (!attr_set) {
+    ALS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES));
+    attr_set = true;
+  }
+  dim3 grid(a.tiles_m * a.tiles_n * nsplit);
+  ProfRec rec;
+  bool prof = false;
+  if (g_prof_on) {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (g_prof_on && (g_prof_count++ % (unsigned)g_prof_every) == 0 && hipEventCreate(&rec.e0) == hipSuccess) {
+      if (hipEventCreate(&rec.e1) == hipSuccess) prof = true;
+      else (void)hipEventDestroy(rec.e0);
+    }
+  }
+  if (prof) hipExtLaunchKernelGGL(kern, grid, dim3(512), TL::LDS_BYTES, st, rec.e0, rec.e1, 0, a);
+  else hipLaunchKernelGGL(kern, grid, dim3(512), TL::LDS_BYTES, st, a);
+  ALS_CHECK_LAUNCH();
+  if (prof) {
+    rec.id = kernel_id(256, 256, AL, BL, EPI, sizeof(TO) == 2, SPLIT, 4);
+    rec.flops = 2.0 * a.M * a.N * (double)a.K * nsplit;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    g_prof.push_back(rec);
+  }
+  return ALS_OK;
+}
+
 inline bool fits(int M, int N, int bm, int bn) { return M % bm == 0 && N % bn == 0; }
 
 }  // namespace
@@ -458,6 +710,7 @@ bool gemm_mfma_supported(const GemmDesc& g) {
 // double-buffered or single-buffered with 2 / 3 workgroups per CU
 #define ALS_TILE_SWITCH(AL, BL, EPI, TO, SPLIT)                                                            \
   do {                                                                                                     \
+    if (bm == 256 && bn == 256 && nbuf == 4) return launch_pp<AL, BL, EPI, TO, SPLIT>(a, nsplit, st);      \
     if (bm == 256 && bn == 256) return launch<256, 256, AL, BL, EPI, TO, SPLIT, 2, 1>(a, nsplit, st);      \
     if (bm == 256 && bn == 128 && nbuf == 2) return launch<256, 128, AL, BL, EPI, TO, SPLIT, 2, 1>(a, nsplit, st); \
     if (bm == 256 && bn == 128 && nbuf == 1) return launch<256, 128, AL, BL, EPI, TO, SPLIT, 1, 2>(a, nsplit, st);      \
@@ -491,8 +744,21 @@ int gemm_mfma(const GemmDesc& g, hipStream_t st) {
   // the double-buffered one once K is long enough to amortise its single resident pair;
   // 256x128 (less operand traffic and fewer LDS bytes per flop) when its tiles fill at least
   // 7/8 of the 512 resident slots (2 per CU).
+  // The 256x256 kernel with two wavefront groups in alternating phases (buffering code 4; it
+  // masks partial tiles, so M and N need only be multiples of 128) moves a third less operand data
+  // per flop than 256x128 and keeps the matrix pipes busy through its LDS traffic; it runs one
+  // workgroup per CU, so it needs enough tiles to fill the chip and enough K per tile to amortise
+  // a prologue and an epilogue that nothing overlaps.  Measured against the other variants on the
+  // 150M-class and 20M-class shapes (profiles/gemm_mfma_microbench.md): it wins from about 7/8 of a
+  // round of 256 tiles unless both K and the tile count are small; weight gradients (split along
+  // K) from a few dozen tiles.
   int bm = 128, bn = 128, nbuf = 1;
-  if (g_force_bm && fits(g.M, g.N, g_force_bm, g_force_bn)) { bm = g_force_bm; bn = g_force_bn; nbuf = g_force_nbuf; }
+  const int t256 = ((g.M + 255) / 256) * ((g.N + 255) / 256);
+  const bool pp_pays = g.a_layout == 1 ? t256 >= 24
+                                       : t256 >= 224 && !(g.K < 768 && t256 < 1024) && !(g.K < 1024 && g.N < 1024);
+  if (g_force_bm && g_force_nbuf == 4) { bm = 256; bn = 256; nbuf = 4; }
+  else if (g_force_bm && fits(g.M, g.N, g_force_bm, g_force_bn)) { bm = g_force_bm; bn = g_force_bn; nbuf = g_force_nbuf; }
+  else if (!g_force_bm && pp_pays) { bm = 256; bn = 256; nbuf = 4; }
   else if (g.a_layout == 1) {
     if (fits(g.M, g.N, 256, 256) && (g.M / 256) * (g.N / 256) >= 64) { bm = 256; bn = 256; nbuf = 2; }
     else if (fits(g.M, g.N, 256, 128) && (g.M / 256) * (g.N / 128) >= 128) { bm = 256; bn = 128; nbuf = 1; }
@@ -501,7 +767,7 @@ int gemm_mfma(const GemmDesc& g, hipStream_t st) {
   else if (g.K >= 2048) nbuf = 2;
   MfmaArgs a;
   a.A = (const bf16*)g.A; a.B = (const bf16*)g.B; a.lda = g.lda; a.ldb = g.ldb;
-  a.M = g.M; a.N = g.N; a.K = g.K; a.tiles_m = g.M / bm; a.tiles_n = g.N / bn;
+  a.M = g.M; a.N = g.N; a.K = g.K; a.tiles_m = (g.M + bm - 1) / bm; a.tiles_n = (g.N + bn - 1) / bn;
   a.C = g.C; a.ldc = g.ldc; a.R = g.R; a.ldr = g.ldr; a.C2 = g.C2; a.U = (const bf16*)g.U;
   a.split_stride = 0; a.nsplit = 1;
   int nsplit = 1;
@@ -590,6 +856,11 @@ extern "C" int als_prof_kernel_name(int id, char* out, int out_len) {
   static const char* epi[4] = {"STORE", "RESID", "GELU", "DGELU"};
   int nbuf = ((id >> 8) & 3) + 1, bm = ((id & 1) + 1) * 128, bn = (((id >> 1) & 1) + 1) * 128;
   int occ = nbuf == 2 ? (bm == 128 ? 2 : 1) : nbuf == 3 ? 2 : (bm == 256 ? 2 : 3);
+  if (nbuf == 4) {
+    snprintf(out, out_len, "gemm_pp_kernel<%d, %d, %s, %s, %s>", (id >> 2) & 1, (id >> 3) & 1, epi[(id >> 4) & 3],
+             (id >> 6) & 1 ? "bf16" : "float", (id >> 7) & 1 ? "true" : "false");
+    return ALS_OK;
+  }
   snprintf(out, out_len, "gemm_mfma_kernel<%d, %d, %d, %d, %s, %s, %s, %d, %d>", bm, bn, (id >> 2) & 1, (id >> 3) & 1,
            epi[(id >> 4) & 3], (id >> 6) & 1 ? "bf16" : "float", (id >> 7) & 1 ? "true" : "false", nbuf, occ);
   return ALS_OK;
@@ -599,7 +870,7 @@ extern "C" int als_prof_kernel_name(int id, char* out, int out_len) {
 // (2 = double, 1 = single buffer with more workgroups per CU); 0,0 restores the automatic choice.  Not thread-safe; meant for benchmarks.
 extern "C" int als_k_set_gemm_tile(int bm, int bn, int nbuf) {
   bool ok = (bm == 0 && bn == 0) || (bm == 256 && bn == 256) || (bm == 256 && bn == 128) || (bm == 128 && bn == 128);
-  if (!ok || (bm && nbuf != 1 && nbuf != 2 && !(nbuf == 3 && bm == 128))) return als::set_error(ALS_ERR_INVALID, "unsupported tile %dx%d/%d", bm, bn, nbuf);
+  if (!ok || (bm && nbuf != 1 && nbuf != 2 && !(nbuf == 3 && bm == 128) && !(nbuf == 4 && bm == 256 && bn == 256))) return als::set_error(ALS_ERR_INVALID, "unsupported tile %dx%d/%d", bm, bn, nbuf);
   als::g_force_bm = bm; als::g_force_bn = bn; als::g_force_nbuf = nbuf;
   return ALS_OK;
 }
