@@ -184,25 +184,68 @@ __global__ __launch_bounds__(256) void dn_group_kernel(float* theta, float* m, f
         if (touch_m) mm[u] = ldnt(m, i);
       }
     }
-    for (int j = 0; j < g.G; j++) {
-      f32x4 ts[U], tw[U];
+    if constexpr (U == 4) {   // one or two events: everything is requested at once
+      for (int j = 0; j < g.G; j++) {
+        f32x4 ts[U], tw[U];
 #pragma unroll
-      for (int u = 0; u < U; u++) {
-        int64_t i = i0 + u * 256;
-        if (i < n4) { ts[u] = ldnt(g.theta_start[j], i); tw[u] = ldnt(g.theta_worker[j], i); }
+        for (int u = 0; u < U; u++) {
+          int64_t i = i0 + u * 256;
+          if (i < n4) { ts[u] = ldnt(g.theta_start[j], i); tw[u] = ldnt(g.theta_worker[j], i); }
+        }
+        const bool boundary = (g.boundary_mask >> j) & 1u;
+        const float wj = g.weight[j];
+#pragma unroll
+        for (int u = 0; u < U; u++)
+          if (i0 + u * 256 < n4) {
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+              float t = th[u][e], mo = mm[u][e], d = de[u][e];
+              dn_event_scalar(t, mo, d, ts[u][e], tw[u][e], boundary, use_m, wj, g);
+              th[u][e] = t; mm[u][e] = mo; de[u][e] = d;
+            }
+          }
       }
-      const bool boundary = (g.boundary_mask >> j) & 1u;
-      const float wj = g.weight[j];
+    } else {
+    // Events are taken four at a time, and the worker vectors of the NEXT four are requested
+    // before the current four are applied: the loop over events has a run-time trip count, and
+    // without this every event would wait for its own two loads with nothing else in flight.
+    f32x4 tsA[4][U], twA[4][U], tsB[4][U], twB[4][U];
+    auto load4 = [&](int j0, f32x4 (&ts)[4][U], f32x4 (&tw)[4][U]) {
 #pragma unroll
-      for (int u = 0; u < U; u++)
-        if (i0 + u * 256 < n4) {
+      for (int jj = 0; jj < 4; jj++)
+        if (j0 + jj < g.G) {
 #pragma unroll
-          for (int e = 0; e < 4; e++) {
-            float t = th[u][e], mo = mm[u][e], d = de[u][e];
-            dn_event_scalar(t, mo, d, ts[u][e], tw[u][e], boundary, use_m, wj, g);
-            th[u][e] = t; mm[u][e] = mo; de[u][e] = d;
+          for (int u = 0; u < U; u++) {
+            int64_t i = i0 + u * 256;
+            if (i < n4) { ts[jj][u] = ldnt(g.theta_start[j0 + jj], i); tw[jj][u] = ldnt(g.theta_worker[j0 + jj], i); }
           }
         }
+    };
+    auto apply4 = [&](int j0, const f32x4 (&ts)[4][U], const f32x4 (&tw)[4][U]) {
+#pragma unroll
+      for (int jj = 0; jj < 4; jj++)
+        if (j0 + jj < g.G) {
+          const bool boundary = (g.boundary_mask >> (j0 + jj)) & 1u;
+          const float wj = g.weight[j0 + jj];
+#pragma unroll
+          for (int u = 0; u < U; u++)
+            if (i0 + u * 256 < n4) {
+#pragma unroll
+              for (int e = 0; e < 4; e++) {
+                float t = th[u][e], mo = mm[u][e], d = de[u][e];
+                dn_event_scalar(t, mo, d, ts[jj][u][e], tw[jj][u][e], boundary, use_m, wj, g);
+                th[u][e] = t; mm[u][e] = mo; de[u][e] = d;
+              }
+            }
+        }
+    };
+    load4(0, tsA, twA);
+    for (int j0 = 0; j0 < g.G; j0 += 8) {
+      if (j0 + 4 < g.G) load4(j0 + 4, tsB, twB);
+      apply4(j0, tsA, twA);
+      if (j0 + 8 < g.G) load4(j0 + 8, tsA, twA);
+      if (j0 + 4 < g.G) apply4(j0 + 4, tsB, twB);
+    }
     }
 #pragma unroll
     for (int u = 0; u < U; u++) {
@@ -237,21 +280,69 @@ __global__ void dn_group_tail_kernel(float* theta, float* m, float* delta, DnGro
     }
 }
 
-int dn_group(float* theta, float* m, float* delta, const DnGroup& g, int64_t P, hipStream_t st) {
+// Restart of the G workers of a group from the new theta as a pass of its own: read 4, write 10 G
+// bytes per parameter.  A write-dominated pass runs closer to the HBM peak than the same writes
+// mixed into the event pass (whose 2 G + 3 read streams and 3 G + 3 write streams together reached
+// 61-64 % of the peak; the event pass alone runs at the single-event rate, this one near the
+// write-only rate), which more than pays for reading theta once more.
+__global__ __launch_bounds__(256) void restart_group_kernel(const float* __restrict__ theta, DnGroup g, int64_t P) {
+  const int64_t n4 = P / 4;
+  const int64_t stride = (int64_t)gridDim.x * 256 * STREAM_U;
+  for (int64_t i0 = (int64_t)blockIdx.x * 256 * STREAM_U + threadIdx.x; i0 < n4; i0 += stride) {
+    f32x4 t[STREAM_U];
+#pragma unroll
+    for (int u = 0; u < STREAM_U; u++)
+      if (i0 + u * 256 < n4) t[u] = ldnt(theta, i0 + u * 256);
+    for (int j = 0; j < g.G; j++) {
+#pragma unroll
+      for (int u = 0; u < STREAM_U; u++)
+        if (i0 + u * 256 < n4) reinterpret_cast<f32x4*>(g.theta_worker[j])[i0 + u * 256] = t[u];
+#pragma unroll
+      for (int u = 0; u < STREAM_U; u++)
+        if (i0 + u * 256 < n4) reinterpret_cast<f32x4*>(g.start_out[j])[i0 + u * 256] = t[u];
+      if (g.lp_out[j]) {
+#pragma unroll
+        for (int u = 0; u < STREAM_U; u++)
+          if (i0 + u * 256 < n4) {
+            bf16x4 o;
+            o[0] = (bf16)t[u][0]; o[1] = (bf16)t[u][1]; o[2] = (bf16)t[u][2]; o[3] = (bf16)t[u][3];
+            reinterpret_cast<bf16x4*>(g.lp_out[j])[i0 + u * 256] = o;
+          }
+      }
+    }
+  }
+  if (blockIdx.x == 0) {
+    for (int64_t i = n4 * 4 + threadIdx.x; i < P; i += blockDim.x) {
+      float t = theta[i];
+      for (int j = 0; j < g.G; j++) {
+        g.theta_worker[j][i] = t; g.start_out[j][i] = t;
+        if (g.lp_out[j]) g.lp_out[j][i] = (bf16)t;
+      }
+    }
+  }
+}
+
+int dn_group(float* theta, float* m, float* delta, const DnGroup& g_in, int64_t P, hipStream_t st) {
+  // groups of more than two workers: events first, then the restart as its own pass
+  const bool split_restart = g_in.restart && g_in.G > 2;
+  DnGroup g = g_in;
+  if (split_restart) g.restart = 0;
   if (g.G < 1 || g.G > ALS_DN_MAX_GROUP) return set_error(ALS_ERR_INVALID, "dn_group: G out of range");
   if (P <= 0) return ALS_OK;
   int64_t n4 = P / 4;
   if (n4 > 0) {
     if (g.G <= 2)
       hipLaunchKernelGGL(dn_group_kernel<4>, dim3(stream_blocks(n4, 4)), dim3(256), 0, st, theta, m, delta, g, n4);
-    else if (g.G <= 4)
-      hipLaunchKernelGGL(dn_group_kernel<2>, dim3(stream_blocks(n4, 2)), dim3(256), 0, st, theta, m, delta, g, n4);
     else
-      hipLaunchKernelGGL(dn_group_kernel<1>, dim3(stream_blocks(n4, 1)), dim3(256), 0, st, theta, m, delta, g, n4);
+      hipLaunchKernelGGL(dn_group_kernel<2>, dim3(stream_blocks(n4, 2)), dim3(256), 0, st, theta, m, delta, g, n4);
     ALS_CHECK_LAUNCH();
   }
   if (n4 * 4 < P) {
     hipLaunchKernelGGL(dn_group_tail_kernel, dim3(1), dim3(64), 0, st, theta, m, delta, g, n4 * 4, P);
+    ALS_CHECK_LAUNCH();
+  }
+  if (split_restart) {
+    hipLaunchKernelGGL(restart_group_kernel, dim3(stream_blocks(n4 > 0 ? n4 : 1, STREAM_U)), dim3(256), 0, st, theta, g, P);
     ALS_CHECK_LAUNCH();
   }
   return ALS_OK;
