@@ -119,26 +119,48 @@ def gelu_grad(u):
     return t(0.5) * (t(1.0) + th) + t(0.5) * u * (t(1.0) - th * th) * inner
 
 
-def attention_fwd(q, k, v):
+def round_bf16(x):
+    """float32 array rounded to the nearest bfloat16 value (ties to even), returned as float32:
+    add 0x7FFF plus the lowest kept mantissa bit to the bit pattern and clear the low 16 bits."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    r = (u + (((u >> 16) & np.uint32(1)) + np.uint32(0x7FFF))) & np.uint32(0xFFFF0000)
+    return r.view(np.float32)
+
+
+def _operands(cfg):
+    """What happens to the two operands of every matrix product before it is formed.  By default
+    nothing.  cfg["operand_rounding"] = "bf16" rounds both to bfloat16 (the product itself is still
+    accumulated in the array dtype, float32): the precision policy "bf16 in, fp32 accumulate"
+    applied to the oracle's own products, used to measure how far a correct implementation with
+    bf16 operands may sit from the plain float32 result."""
+    kind = cfg.get("operand_rounding")
+    if kind is None:
+        return lambda x: x
+    if kind == "bf16":
+        return round_bf16
+    raise ValueError(f"unknown operand rounding {kind!r}")
+
+
+def attention_fwd(q, k, v, rnd=lambda x: x):
     """q,k,v [B,h,S,dh] -> o [B,h,S,dh], p [B,h,S,S] (causal softmax probabilities)."""
     S, dh = q.shape[2], q.shape[3]
-    s = np.matmul(q, np.swapaxes(k, -1, -2)) * q.dtype.type(1.0 / math.sqrt(dh))
+    s = np.matmul(rnd(q), np.swapaxes(rnd(k), -1, -2)) * q.dtype.type(1.0 / math.sqrt(dh))
     mask = np.triu(np.ones((S, S), dtype=bool), k=1)
     s = np.where(mask, -np.inf, s)
     s = s - np.max(s, axis=-1, keepdims=True)
     p = np.exp(s)
     p = p / np.sum(p, axis=-1, keepdims=True)
-    return np.matmul(p, v), p
+    return np.matmul(rnd(p), rnd(v)), p
 
 
-def attention_bwd(do, q, k, v, p):
+def attention_bwd(do, q, k, v, p, rnd=lambda x: x):
     dh = q.shape[3]
-    dv = np.matmul(np.swapaxes(p, -1, -2), do)
-    dp = np.matmul(do, np.swapaxes(v, -1, -2))
+    dv = np.matmul(np.swapaxes(rnd(p), -1, -2), rnd(do))
+    dp = np.matmul(rnd(do), np.swapaxes(rnd(v), -1, -2))
     ds = p * (dp - np.sum(dp * p, axis=-1, keepdims=True))
     ds = ds * q.dtype.type(1.0 / math.sqrt(dh))
-    dq = np.matmul(ds, k)
-    dk = np.matmul(np.swapaxes(ds, -1, -2), q)
+    dq = np.matmul(rnd(ds), rnd(k))
+    dk = np.matmul(np.swapaxes(rnd(ds), -1, -2), rnd(q))
     return dq, dk, dv
 
 
@@ -161,6 +183,7 @@ def forward(theta, tokens, cfg, keep=True):
     da = attention_width(cfg)
     eps = cfg["norm_eps"]
     norm_fwd, _ = _norm(cfg)
+    rnd = _operands(cfg)
     B = tokens.shape[0]
     assert tokens.shape[1] == S + 1
     inp, tgt = tokens[:, :S], tokens[:, 1:].reshape(-1)
@@ -168,23 +191,23 @@ def forward(theta, tokens, cfg, keep=True):
     layers = []
     for l in range(L):
         a, rstd1 = norm_fwd(x, p[f"g1{l}"], eps)
-        qkv = a @ p[f"Wqkv{l}"]
+        qkv = rnd(a) @ rnd(p[f"Wqkv{l}"])
         q = _split_heads(qkv[:, :da], B, S, h)
         k = _split_heads(qkv[:, da:2 * da], B, S, h)
         v = _split_heads(qkv[:, 2 * da:], B, S, h)
-        o4, prob = attention_fwd(q, k, v)
+        o4, prob = attention_fwd(q, k, v, rnd)
         o = _merge_heads(o4)
-        xm = x + o @ p[f"Wo{l}"]
+        xm = x + rnd(o) @ rnd(p[f"Wo{l}"])
         b, rstd2 = norm_fwd(xm, p[f"g2{l}"], eps)
-        u = b @ p[f"W1{l}"]
+        u = rnd(b) @ rnd(p[f"W1{l}"])
         gl = gelu_fwd(u)
-        xn = xm + gl @ p[f"W2{l}"]
+        xn = xm + rnd(gl) @ rnd(p[f"W2{l}"])
         if keep:
             layers.append(dict(x=x, a=a, rstd1=rstd1, q=q, k=k, v=v, prob=prob, o=o, xm=xm,
                                b=b, rstd2=rstd2, u=u, gl=gl))
         x = xn
     xf, rstdf = norm_fwd(x, p["gf"], eps)
-    logits = xf @ p["Wout"]
+    logits = rnd(xf) @ rnd(p["Wout"])
     mx = np.max(logits, axis=-1, keepdims=True)
     lse = mx[:, 0] + np.log(np.sum(np.exp(logits - mx), axis=-1))
     T = B * S
@@ -202,31 +225,32 @@ def backward(theta, cache, cfg):
     L, d, h, S = cfg["L"], cfg["d"], cfg["h"], cfg["S"]
     B = cache["B"]
     T = B * S
+    rnd = _operands(cfg)
     logits, lse, tgt = cache["logits"], cache["lse"], cache["tgt"]
     dlogits = np.exp(logits - lse[:, None])
     dlogits[np.arange(T), tgt] -= 1.0
     dlogits = dlogits * theta.dtype.type(1.0 / T)
-    g["Wout"][...] = cache["xf"].T @ dlogits
-    dxf = dlogits @ p["Wout"].T
+    g["Wout"][...] = rnd(cache["xf"]).T @ rnd(dlogits)
+    dxf = rnd(dlogits) @ rnd(p["Wout"]).T
     _, norm_bwd = _norm(cfg)
     dx, dgf = norm_bwd(dxf, cache["x"], cache["rstdf"], p["gf"])
     g["gf"][...] = dgf
     for l in reversed(range(L)):
         c = cache["layers"][l]
-        g[f"W2{l}"][...] = c["gl"].T @ dx
-        dgl = dx @ p[f"W2{l}"].T
+        g[f"W2{l}"][...] = rnd(c["gl"]).T @ rnd(dx)
+        dgl = rnd(dx) @ rnd(p[f"W2{l}"]).T
         du = dgl * gelu_grad(c["u"])
-        g[f"W1{l}"][...] = c["b"].T @ du
-        db = du @ p[f"W1{l}"].T
+        g[f"W1{l}"][...] = rnd(c["b"]).T @ rnd(du)
+        db = rnd(du) @ rnd(p[f"W1{l}"]).T
         dxm_n, dg2 = norm_bwd(db, c["xm"], c["rstd2"], p[f"g2{l}"])
         g[f"g2{l}"][...] = dg2
         dxm = dx + dxm_n
-        g[f"Wo{l}"][...] = c["o"].T @ dxm
-        do = _split_heads(dxm @ p[f"Wo{l}"].T, B, S, h)
-        dq, dk, dv = attention_bwd(do, c["q"], c["k"], c["v"], c["prob"])
+        g[f"Wo{l}"][...] = rnd(c["o"]).T @ rnd(dxm)
+        do = _split_heads(rnd(dxm) @ rnd(p[f"Wo{l}"]).T, B, S, h)
+        dq, dk, dv = attention_bwd(do, c["q"], c["k"], c["v"], c["prob"], rnd)
         dqkv = np.concatenate([_merge_heads(dq), _merge_heads(dk), _merge_heads(dv)], axis=1)
-        g[f"Wqkv{l}"][...] = c["a"].T @ dqkv
-        da = dqkv @ p[f"Wqkv{l}"].T
+        g[f"Wqkv{l}"][...] = rnd(c["a"]).T @ rnd(dqkv)
+        da = rnd(dqkv) @ rnd(p[f"Wqkv{l}"]).T
         dx_n, dg1 = norm_bwd(da, c["x"], c["rstd1"], p[f"g1{l}"])
         g[f"g1{l}"][...] = dg1
         dx = dxm + dx_n

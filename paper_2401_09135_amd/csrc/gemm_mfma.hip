@@ -596,6 +596,175 @@ __global__ __launch_bounds__(512, 1) void gemm_pp_kernel(MfmaArgs g) {
   ep.run(acc, smem + wave * (32 * EP::PITCH), C);
 }
 
+// ---- the same ping-pong kernel with operands loaded straight from global memory into LDS ------
+// The loads of slice kt + 1 write LDS buffer (kt + 1) & 1 directly (global_load_lds_dwordx4: each
+// wavefront instruction fills 1 KB of LDS, lane l supplying bytes 16 l .. 16 l + 15), so the data
+// never crosses the vector registers and no LDS store instruction is issued.  Rows cannot be padded
+// inside such a 1 KB block, so bank conflicts are avoided by permuting 16-byte chunks inside a tile
+// row instead; the permutation is applied on the global side (which chunk a lane fetches) and undone
+// in the fragment addresses:
+//   contraction-contiguous tile, [256 rows][128 bytes], 8 rows per instruction: row R keeps chunk c
+//     at position c ^ ((R >> 1) & 7) (the 16 rows one quarter of a 16-byte fragment read touches
+//     then fall into 16 different bank groups);
+//   contraction-strided tile, [64 k][512 bytes], 2 k rows per instruction: k row r keeps its 64-byte
+//     group q at position q ^ (r & 3) (the 4 k rows that 32 lanes of a transpose read touch then
+//     fall into 4 different quarters of the banks).
+// These loads are outside the compiler's wait tracking (inline assembly): every wavefront waits
+// for its own (vmcnt(0)) before the last barrier that precedes the first read of the buffer.
+__device__ __forceinline__ void global_to_lds_16(const void* base, unsigned voff, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(base) : "memory");
+}
+
+template <int AL, int BL, int EPI, typename TO, bool SPLIT>
+__global__ __launch_bounds__(512, 1) void gemm_ppd_kernel(MfmaArgs g) {
+  constexpr int BM = 256, BN = 256;
+  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES, LDS_BYTES = 2 * STAGE;
+  constexpr int WM = 128, WN = 64, TM = 4, TN = 2;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int grp = wave >> 2, wm = (wave >> 1) & 1, wn = wave & 1;
+  const int ncol0 = grp * 128 + wn * WN;
+
+  int ntiles = g.tiles_m * g.tiles_n;
+  int id = blockIdx.x, tile, zsplit = 0;
+  if (SPLIT) {
+    zsplit = id % g.nsplit;
+    tile = id / g.nsplit;
+  } else {
+    int per = ntiles / 8;
+    tile = (id < per * 8) ? (id % 8) * per + id / 8 : id;
+  }
+  int tm, tn;
+  {
+    constexpr int GN = 8;
+    const int span = GN * g.tiles_m, b = tile / span, r = tile - b * span;
+    const int width = g.tiles_n - b * GN < GN ? g.tiles_n - b * GN : GN;
+    tm = r / width;
+    tn = b * GN + r % width;
+  }
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int64_t kbase = (int64_t)zsplit * g.K;
+  const int nk = g.K / BK;
+
+  // Wavefront w, instruction i (0..3) moves 1 KB of the A tile and 1 KB of the B tile: tile rows
+  // 8 (4 w + i) .. + 7 (contraction-contiguous) or k rows 2 (4 w + i), + 1 (contraction-strided).
+  const char* Ag = reinterpret_cast<const char*>(AL == 0 ? g.A + (int64_t)m0 * g.lda + kbase : g.A + kbase * g.lda + m0);
+  const char* Bg = reinterpret_cast<const char*>(BL == 1 ? g.B + (int64_t)n0 * g.ldb + kbase : g.B + kbase * g.ldb + n0);
+  const int64_t a_step = AL == 0 ? BK * 2 : (int64_t)BK * g.lda * 2;
+  const int64_t b_step = BL == 1 ? BK * 2 : (int64_t)BK * g.ldb * 2;
+  unsigned a_goff[4], b_goff[4];
+  auto chunk_offset = [&](bool kcontig, int i, int origin, int extent, int64_t ld) -> unsigned {
+    if (kcontig) {
+      const int R = 8 * (4 * wave + i) + (lane >> 3);
+      const int chunk = (lane & 7) ^ ((R >> 1) & 7);
+      const int r = origin + R < extent ? R : extent - 1 - origin;
+      return (unsigned)((int64_t)r * ld * 2 + chunk * 16);
+    }
+    const int kr = 2 * (4 * wave + i) + (lane >> 5);
+    const int chunk = (lane & 31) ^ ((kr & 3) << 2);
+    int c = chunk * 8;
+    c = origin + c < extent ? c : extent - 8 - origin;
+    return (unsigned)(((int64_t)kr * ld + c) * 2);
+  };
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    a_goff[i] = chunk_offset(AL == 0, i, m0, g.M, g.lda);
+    b_goff[i] = chunk_offset(BL == 1, i, n0, g.N, g.ldb);
+  }
+  const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)(smem);
+  auto issue_loads = [&](int kt) {   // slice kt into buffer kt & 1
+    const char* ap = Ag + kt * a_step;
+    const char* bp = Bg + kt * b_step;
+    const unsigned dst = lds0 + (kt & 1) * STAGE + (4 * wave) * 1024;
+#pragma unroll
+    for (int i = 0; i < 4; i++) global_to_lds_16(ap, a_goff[i], dst + i * 1024);
+#pragma unroll
+    for (int i = 0; i < 4; i++) global_to_lds_16(bp, b_goff[i], dst + A_BYTES + i * 1024);
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int v = 0; v < 16; v++) acc[i][j][v] = 0.0f;
+
+  // Fragment addresses.
+  // contraction-contiguous: row R = base + (lane & 31), k chunk q = 2 kk + (lane >> 5) sits at
+  //   position q ^ f(R), f(R) = ((lane & 31) >> 1) & 7 for every 32-aligned base.
+  // contraction-strided (transpose read): k row = 16 kk + 8 (lane >> 5) + ((lane & 15) >> 2) (+ 4 for
+  //   the second half), so k row & 3 = (lane >> 2) & 3; the 64-byte group (base * 2) >> 6 of a
+  //   32-row block sits at group ^ that.
+  const int fx = ((lane >> 5) ^ (((lane & 31) >> 1) & 7));
+  const int tx = (lane >> 2) & 3;
+  const int tr_row = ((lane >> 5) * 8 + ((lane & 15) >> 2)) * 512 + ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
+  const int a_off = AL == 0 ? (wm * WM + (lane & 31)) * 128 : tr_row + wm * 256;
+  const int b_off = BL == 1 ? (ncol0 + (lane & 31)) * 128 : tr_row + grp * 256;
+  bf16x8 af[2][TM], bfr[2][TN];
+  auto memory_phase = [&](int kt, int h) {
+    const char* As = smem + (kt & 1) * STAGE;
+    const char* Bs = As + A_BYTES;
+#pragma unroll
+    for (int s2 = 0; s2 < 2; s2++) {
+      const int kk = 2 * h + s2;
+      const int pos = ((kk * 2) ^ fx) * 16;
+#pragma unroll
+      for (int j = 0; j < TN; j++) {
+        if (BL == 1) bfr[s2][j] = lds_read_direct(Bs + b_off + j * 32 * 128 + pos);
+        else bfr[s2][j] = lds_read_tr(Bs + b_off + kk * 16 * 512 + (((wn * 2 + j) ^ tx) << 6), 512);
+      }
+#pragma unroll
+      for (int i = 0; i < TM; i++) {
+        if (AL == 0) af[s2][i] = lds_read_direct(As + a_off + i * 32 * 128 + pos);
+        else af[s2][i] = lds_read_tr(As + a_off + kk * 16 * 512 + ((i ^ tx) << 6), 512);
+      }
+    }
+    if (h == 0 && kt + 1 < nk) issue_loads(kt + 1);
+  };
+  auto compute_phase = [&]() {
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+    for (int s2 = 0; s2 < 2; s2++)
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[s2][j], af[s2][i], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  issue_loads(0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (grp == 1) __builtin_amdgcn_s_barrier();   // group 1 runs one phase behind group 0
+  for (int kt = 0; kt < nk; kt++) {
+#pragma unroll
+    for (int h = 0; h < 2; h++) {
+      memory_phase(kt, h);
+      // Slice kt + 1 is first read in group 0's next memory phase, p = 4 kt + 4.  The last barrier
+      // before it is, for group 1, the one that ends this memory phase when h == 1; for group 0
+      // the one after its compute phase below.
+      if (h == 1 && grp == 1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      compute_phase();
+      if (h == 1 && grp == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      if (!(grp == 1 && kt == nk - 1 && h == 1)) __builtin_amdgcn_s_barrier();
+    }
+  }
+
+  if (m0 + wm * WM >= g.M || n0 + ncol0 >= g.N) return;   // sub-tile outside the matrix
+  TO* C = reinterpret_cast<TO*>(g.C);
+  if (SPLIT) C += (int64_t)zsplit * g.split_stride;
+  typedef WaveEpilogue<TM, TN, WN, EPI, TO> EP;
+  static_assert(8 * 32 * EP::PITCH <= LDS_BYTES, "epilogue staging must fit the operand buffers");
+  EP ep(g, lane, m0 + wm * WM, n0 + ncol0);
+  ep.preload();
+  ep.run(acc, smem + wave * (32 * EP::PITCH), C);
+}
+
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part,
                                                             float* __restrict__ C, int64_t n4,
                                                             int nsplit, int64_t stride4) {
@@ -684,6 +853,37 @@ int launch_pp(const MfmaArgs& a, int nsplit, hipStream_t st) {
   return ALS_OK;
 }
 
+template <int AL, int BL, int EPI, typename TO, bool SPLIT>
+int launch_ppd(const MfmaArgs& a, int nsplit, hipStream_t st) {
+  constexpr int LDS = 2 * (256 * 128 + 256 * 128);
+  auto kern = gemm_ppd_kernel<AL, BL, EPI, TO, SPLIT>;
+  static bool attr_set = false;  // idempotent; a race only repeats the call
+  if (!attr_set) {
+    ALS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS));
+    attr_set = true;
+  }
+  dim3 grid(a.tiles_m * a.tiles_n * nsplit);
+  ProfRec rec;
+  bool prof = false;
+  if (g_prof_on) {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (g_prof_on && (g_prof_count++ % (unsigned)g_prof_every) == 0 && hipEventCreate(&rec.e0) == hipSuccess) {
+      if (hipEventCreate(&rec.e1) == hipSuccess) prof = true;
+      else (void)hipEventDestroy(rec.e0);
+    }
+  }
+  if (prof) hipExtLaunchKernelGGL(kern, grid, dim3(512), LDS, st, rec.e0, rec.e1, 0, a);
+  else hipLaunchKernelGGL(kern, grid, dim3(512), LDS, st, a);
+  ALS_CHECK_LAUNCH();
+  if (prof) {
+    rec.id = kernel_id(256, 256, AL, BL, EPI, sizeof(TO) == 2, SPLIT, 4);
+    rec.flops = 2.0 * a.M * a.N * (double)a.K * nsplit;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    g_prof.push_back(rec);
+  }
+  return ALS_OK;
+}
+
 inline bool fits(int M, int N, int bm, int bn) { return M % bm == 0 && N % bn == 0; }
 
 }  // namespace
@@ -711,6 +911,7 @@ bool gemm_mfma_supported(const GemmDesc& g) {
 #define ALS_TILE_SWITCH(AL, BL, EPI, TO, SPLIT)                                                            \
   do {                                                                                                     \
     if (bm == 256 && bn == 256 && nbuf == 4) return launch_pp<AL, BL, EPI, TO, SPLIT>(a, nsplit, st);      \
+    if (bm == 256 && bn == 256 && nbuf == 5) return launch_ppd<AL, BL, EPI, TO, SPLIT>(a, nsplit, st);     \
     if (bm == 256 && bn == 256) return launch<256, 256, AL, BL, EPI, TO, SPLIT, 2, 1>(a, nsplit, st);      \
     if (bm == 256 && bn == 128 && nbuf == 2) return launch<256, 128, AL, BL, EPI, TO, SPLIT, 2, 1>(a, nsplit, st); \
     if (bm == 256 && bn == 128 && nbuf == 1) return launch<256, 128, AL, BL, EPI, TO, SPLIT, 1, 2>(a, nsplit, st);      \
@@ -755,10 +956,11 @@ int gemm_mfma(const GemmDesc& g, hipStream_t st) {
   int bm = 128, bn = 128, nbuf = 1;
   const int t256 = ((g.M + 255) / 256) * ((g.N + 255) / 256);
   const bool pp_pays = g.a_layout == 1 ? t256 >= 24
-                                       : t256 >= 224 && !(g.K < 768 && t256 < 1024) && !(g.K < 1024 && g.N < 1024);
+                                       : t256 >= 224 && !(g.K < 768 && t256 < 1024);
   if (g_force_bm && g_force_nbuf == 4) { bm = 256; bn = 256; nbuf = 4; }
+  else if (g_force_bm && g_force_nbuf == 5) { bm = 256; bn = 256; nbuf = 5; }
   else if (g_force_bm && fits(g.M, g.N, g_force_bm, g_force_bn)) { bm = g_force_bm; bn = g_force_bn; nbuf = g_force_nbuf; }
-  else if (!g_force_bm && pp_pays) { bm = 256; bn = 256; nbuf = 4; }
+  else if (!g_force_bm && pp_pays) { bm = 256; bn = 256; nbuf = 5; }
   else if (g.a_layout == 1) {
     if (fits(g.M, g.N, 256, 256) && (g.M / 256) * (g.N / 256) >= 64) { bm = 256; bn = 256; nbuf = 2; }
     else if (fits(g.M, g.N, 256, 128) && (g.M / 256) * (g.N / 128) >= 128) { bm = 256; bn = 128; nbuf = 1; }
@@ -870,7 +1072,7 @@ extern "C" int als_prof_kernel_name(int id, char* out, int out_len) {
 // (2 = double, 1 = single buffer with more workgroups per CU); 0,0 restores the automatic choice.  Not thread-safe; meant for benchmarks.
 extern "C" int als_k_set_gemm_tile(int bm, int bn, int nbuf) {
   bool ok = (bm == 0 && bn == 0) || (bm == 256 && bn == 256) || (bm == 256 && bn == 128) || (bm == 128 && bn == 128);
-  if (!ok || (bm && nbuf != 1 && nbuf != 2 && !(nbuf == 3 && bm == 128) && !(nbuf == 4 && bm == 256 && bn == 256))) return als::set_error(ALS_ERR_INVALID, "unsupported tile %dx%d/%d", bm, bn, nbuf);
+  if (!ok || (bm && nbuf != 1 && nbuf != 2 && !(nbuf == 3 && bm == 128) && !((nbuf == 4 || nbuf == 5) && bm == 256 && bn == 256))) return als::set_error(ALS_ERR_INVALID, "unsupported tile %dx%d/%d", bm, bn, nbuf);
   als::g_force_bm = bm; als::g_force_bn = bn; als::g_force_nbuf = nbuf;
   return ALS_OK;
 }

@@ -9,9 +9,12 @@ from .binding import Config, Context, dylu_schedule
 
 
 def run_async(w: dict, theta0: np.ndarray, make_stream, n_events: int | None = None, flags: int = 0,
-              ctx: Context | None = None, collect_losses: bool = True, lr=None, rule: dict | None = None):
+              ctx: Context | None = None, collect_losses: bool = True, lr=None, rule: dict | None = None,
+              on_group=None):
     """w: workload dict (als_inputs.workload); make_stream(i) -> object with take(n) giving
-    int32 [n,B,S+1] token batches for worker i.  Returns dict like the oracle's run."""
+    int32 [n,B,S+1] token batches for worker i.  Returns dict like the oracle's run.
+    on_group(ctx, index of the group's last event): optional observer called after every applied
+    group of sync events (before its workers are given new rounds)."""
     import torch
     n_events = w["n_events"] if n_events is None else n_events
     steps, ev_w, ev_t, ev_g = dylu_schedule(w["speeds"], w["H"], w["tau_grace"], n_events)
@@ -50,6 +53,8 @@ def run_async(w: dict, theta0: np.ndarray, make_stream, n_events: int | None = N
             ctx.outer_apply_rule(group, restart=complete, **rule)
         else:
             ctx.outer_apply_dn(group, restart=complete)
+        if on_group is not None:
+            on_group(ctx, j)
         if complete and j + 1 < n_events:
             for i in group:
                 train(i)

@@ -61,6 +61,7 @@ def main():
     ap.add_argument("--per-tensor", type=int, default=4096)
     ap.add_argument("--ev-stride", type=int, default=4)
     ap.add_argument("--out", default=None)
+    ap.add_argument("--progress-every", type=int, default=4)
     a = ap.parse_args()
     w = I.workload(a.workload)
     if a.H is not None:
@@ -81,8 +82,20 @@ def main():
             print(f"[{time.time() - t0:8.0f} s] worker round of {n} steps starts", flush=True)
             return super().take(n)
 
+    # a progress line every few local steps (the oracle's own loss-and-gradient routine, counted)
+    inner, count = lm.loss_and_grad, [0]
+
+    def counted(theta, tokens, cfg):
+        out = inner(theta, tokens, cfg)
+        count[0] += 1
+        if count[0] % a.progress_every == 0:
+            print(f"[{time.time() - t0:8.0f} s] {count[0]} local steps done, last loss {float(out[0]):.4f}", flush=True)
+        return out
+    lm.loss_and_grad = counted
+
     ref = run.run_async(w, theta0, lambda i: Stream(w["seed"], i, w["B"], w["S"], w["V"]),
                         n_events=n_events, log=log)
+    lm.loss_and_grad = inner
     ev = [(wk, t) for g in ref["groups"] for (wk, t) in g["events"]]
     out = dict(H=np.int64(w["H"]), n_events=np.int64(n_events), steps=np.asarray(ref["steps"], np.int64),
                ev_worker=np.asarray([e[0] for e in ev], np.int64), ev_time=np.asarray([e[1] for e in ev], np.float64),

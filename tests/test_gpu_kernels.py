@@ -306,9 +306,10 @@ def test_gemm_mfma_random_shapes_layouts_and_tiles(seed):
     rng = np.random.default_rng([seed, 0x6E])
     al, bl = [(0, 0), (0, 1), (1, 0)][int(rng.integers(0, 3))]
     tile = [(0, 0, 0), (256, 256, 2), (256, 128, 2), (256, 128, 1), (128, 128, 2), (128, 128, 1), (128, 128, 3),
-            (256, 256, 4), (256, 256, 4)][int(rng.integers(0, 9))]
-    # (buffering code 4 = the 256 x 256 kernel with two wavefront groups in alternating phases; it masks partial tiles)
-    unit_m, unit_n = (128, 128) if tile[2] == 4 else (max(tile[0], 128), max(tile[1], 128))
+            (256, 256, 4), (256, 256, 5)][int(rng.integers(0, 9))]
+    # (buffering codes 4, 5 = the 256 x 256 kernel with two wavefront groups in alternating phases, 5 with
+    # operands loaded straight into LDS where the layout allows; both mask partial tiles)
+    unit_m, unit_n = (128, 128) if tile[2] >= 4 else (max(tile[0], 128), max(tile[1], 128))
     M, N = unit_m * int(rng.integers(1, 5)), unit_n * int(rng.integers(1, 5))
     K = 64 * int(rng.integers(1, 48))
     out_bf16 = bool(rng.integers(0, 2)) and al == 0
@@ -342,7 +343,7 @@ def test_gemm_mfma_tile_variants_agree():
     b = _dev(rng.standard_normal((K, N)).astype(np.float32), torch.bfloat16)
     ref = a.float().cpu().numpy().astype(np.float64) @ b.float().cpu().numpy().astype(np.float64)
     try:
-        for tile in [(256, 256, 2), (256, 128, 2), (256, 128, 1), (128, 128, 2), (128, 128, 1), (128, 128, 3), (256, 256, 4)]:
+        for tile in [(256, 256, 2), (256, 128, 2), (256, 128, 1), (128, 128, 2), (128, 128, 1), (128, 128, 3), (256, 256, 4), (256, 256, 5)]:
             A.lib.als_k_set_gemm_tile(*tile)
             c = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
             A.k_gemm(a, b, c, M, N, K, 0, 0, use_mfma=True)

@@ -198,3 +198,26 @@ def test_pieces_against_library():
     np.testing.assert_allclose(dx.sum(axis=1), 0.0, atol=1e-13)
     xc = x - x.mean(axis=1, keepdims=True)
     np.testing.assert_allclose((dx * xc).sum(axis=1), 1e-5 * rstd[:, 0] ** 2 * (dy * g * xc * rstd).sum(axis=1), atol=1e-14)
+
+
+def test_bf16_operand_rounding_matches_the_library_conversion_and_perturbs_little():
+    """oracle.lm.round_bf16 equals the library's float32 -> bfloat16 -> float32 conversion (round to
+    nearest, ties to even) on random values, exact ties, subnormal-sized and large values; the
+    oracle with bf16-rounded operands stays within a few 1e-3 of the plain one (8 mantissa bits),
+    and is not identical to it."""
+    import torch
+    rng = np.random.default_rng(5)
+    x = np.concatenate([rng.standard_normal(100000).astype(np.float32) * np.float32(3.0),
+                        np.float32([0.0, -0.0, 1.0, 1.00390625, 1.01171875, -1.00390625, 3.0e38, 1e-30, -7.5e-20]),
+                        # exact ties: 1 + (2k+1) 2^-8 lies midway between two bfloat16 values
+                        (1.0 + (2 * np.arange(64) + 1) * 2.0 ** -8).astype(np.float32)])
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(lm.round_bf16(x).view(np.uint32), want.view(np.uint32))
+    w = dict(I.workload("tiny"))
+    theta = I.theta0(lm.param_layout(w), 0)
+    tok = I.TokenStream(0, 0, w["B"], w["S"], w["V"]).take(1)[0]
+    l0, g0 = lm.loss_and_grad(theta.copy(), tok, w)
+    l1, g1 = lm.loss_and_grad(theta.copy(), tok, dict(w, operand_rounding="bf16"))
+    assert l0 != l1 and abs(l0 - l1) / abs(l0) < 2e-3
+    rel = np.linalg.norm(g1.astype(np.float64) - g0) / np.linalg.norm(g0.astype(np.float64))
+    assert 1e-4 < rel < 2e-2
