@@ -960,7 +960,12 @@ int gemm_mfma(const GemmDesc& g, hipStream_t st) {
   if (g_force_bm && g_force_nbuf == 4) { bm = 256; bn = 256; nbuf = 4; }
   else if (g_force_bm && g_force_nbuf == 5) { bm = 256; bn = 256; nbuf = 5; }
   else if (g_force_bm && fits(g.M, g.N, g_force_bm, g_force_bn)) { bm = g_force_bm; bn = g_force_bn; nbuf = g_force_nbuf; }
-  else if (!g_force_bm && pp_pays) { bm = 256; bn = 256; nbuf = 5; }
+  // (inside a worker step, with operands that were written by another kernel moments before, the
+  // direct-to-LDS form and the register-staged form run within 1 % of each other; the direct form
+  // is a few per cent ahead on the input-gradient products, whose operands are both
+  // contraction-contiguous, and is used there)
+  else if (!g_force_bm && pp_pays)
+    { bm = 256; bn = 256; nbuf = g_force_nbuf ? g_force_nbuf : (g.a_layout == 0 && g.b_layout == 1 ? 5 : 4); }
   else if (g.a_layout == 1) {
     if (fits(g.M, g.N, 256, 256) && (g.M / 256) * (g.N / 256) >= 64) { bm = 256; bn = 256; nbuf = 2; }
     else if (fits(g.M, g.N, 256, 128) && (g.M / 256) * (g.N / 128) >= 128) { bm = 256; bn = 128; nbuf = 1; }
@@ -1071,6 +1076,9 @@ extern "C" int als_prof_kernel_name(int id, char* out, int out_len) {
 // Tuning hook: force the MFMA GEMM tile (256x256, 256x128 or 128x128) and its LDS buffering
 // (2 = double, 1 = single buffer with more workgroups per CU); 0,0 restores the automatic choice.  Not thread-safe; meant for benchmarks.
 extern "C" int als_k_set_gemm_tile(int bm, int bn, int nbuf) {
+  // (0, 0, 4) / (0, 0, 5): automatic tile choice, but the register-staged (4) or the direct-to-LDS
+  // (5) form of the ping-pong kernel wherever that kernel is chosen
+  if (bm == 0 && bn == 0 && (nbuf == 4 || nbuf == 5)) { als::g_force_bm = 0; als::g_force_bn = 0; als::g_force_nbuf = nbuf; return ALS_OK; }
   bool ok = (bm == 0 && bn == 0) || (bm == 256 && bn == 256) || (bm == 256 && bn == 128) || (bm == 128 && bn == 128);
   if (!ok || (bm && nbuf != 1 && nbuf != 2 && !(nbuf == 3 && bm == 128) && !((nbuf == 4 || nbuf == 5) && bm == 256 && bn == 256))) return als::set_error(ALS_ERR_INVALID, "unsupported tile %dx%d/%d", bm, bn, nbuf);
   als::g_force_bm = bm; als::g_force_bn = bn; als::g_force_nbuf = nbuf;
