@@ -37,7 +37,8 @@ HEADLINE = "lm150m"
 # (profiles/gemm_mfma_microbench.md gives the commands, the calibration of the two factors and the
 # comparison with the algorithmic bytes).  Counters cannot be collected from inside this process, so
 # the figure is carried here, keyed by workload and kernel; a kernel without an entry reports null.
-MEASURED_TRAFFIC_BYTES = {"lm20m": {"gemm_mfma_kernel<128, 128, 1, 0, STORE, float, true, 2, 2>": 99.0e6}}
+MEASURED_TRAFFIC_BYTES = {"lm20m": {"gemm_mfma_kernel<128, 128, 1, 0, STORE, float, true, 2, 2>": 99.0e6},
+                          "lm150m": {"gemm_pp_kernel<1, 0, STORE, float, true>": 249.9e6}}
 
 
 def flops_per_token(w):
@@ -182,7 +183,12 @@ def outer_microbench_line(args):
                                                       "value = one fused pass of 4 Delayed-Nesterov events (N=4, c=0) "
                                                       "with the 4 workers' restart", results=res),
                roofline=dict(bound="hbm", achieved=res[key]["GBps"], peak=PEAK_HBM_GBS, unit="GB/s",
-                             frac=res[key]["GBps"] / PEAK_HBM_GBS, traffic=None, kernel="dn_group_kernel"),
+                             frac=res[key]["GBps"] / PEAK_HBM_GBS,
+                             # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 of the pass's two launches
+                             # (profiles/outer_microbench_dn_adamw.md): the algorithmic 96 bytes per
+                             # parameter plus the restart pass's second read of theta
+                             traffic=(6445674 + 1757813 + 585971 + 5859375) * 1024.0,
+                             kernel="dn_group_kernel<2> + restart_group_kernel"),
                cpu_baseline=None if args.no_cpu_baseline else cpu_baseline_outer(mb))
     print(json.dumps(out))
 
@@ -208,6 +214,14 @@ def gemm_microbench(args):
     import paper_2401_09135_amd as A
     dev = "cuda:0"
     names = [args.shapes_of] if args.shapes_of else [HEADLINE, "lm20m"]
+    # calibration for HBM counter runs: three plain device copies of 2^26 floats (256 MiB read and
+    # 256 MiB written each) appear in a rocprofv3 --pmc run as launches of known traffic
+    cal_src = torch.randn(1 << 26, device=dev)
+    cal_dst = torch.empty_like(cal_src)
+    for _ in range(3):
+        cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
     ws = torch.empty(64 << 20, dtype=torch.uint8, device=dev)     # split-K scratch
     tiles = [(0, 0, 0)] + [tuple(int(x) for x in t.split("x")) for t in args.tiles.split(",") if t]
     rows = []

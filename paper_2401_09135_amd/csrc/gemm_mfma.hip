@@ -876,7 +876,7 @@ int launch_ppd(const MfmaArgs& a, int nsplit, hipStream_t st) {
   else hipLaunchKernelGGL(kern, grid, dim3(512), LDS, st, a);
   ALS_CHECK_LAUNCH();
   if (prof) {
-    rec.id = kernel_id(256, 256, AL, BL, EPI, sizeof(TO) == 2, SPLIT, 4);
+    rec.id = kernel_id(256, 256, AL, BL, EPI, sizeof(TO) == 2, SPLIT, 4) | 1 << 10;   // bit 10: direct-to-LDS form
     rec.flops = 2.0 * a.M * a.N * (double)a.K * nsplit;
     std::lock_guard<std::mutex> lk(g_prof_mu);
     g_prof.push_back(rec);
@@ -1064,7 +1064,7 @@ extern "C" int als_prof_kernel_name(int id, char* out, int out_len) {
   int nbuf = ((id >> 8) & 3) + 1, bm = ((id & 1) + 1) * 128, bn = (((id >> 1) & 1) + 1) * 128;
   int occ = nbuf == 2 ? (bm == 128 ? 2 : 1) : nbuf == 3 ? 2 : (bm == 256 ? 2 : 3);
   if (nbuf == 4) {
-    snprintf(out, out_len, "gemm_pp_kernel<%d, %d, %s, %s, %s>", (id >> 2) & 1, (id >> 3) & 1, epi[(id >> 4) & 3],
+    snprintf(out, out_len, "gemm_pp%s_kernel<%d, %d, %s, %s, %s>", (id >> 10) & 1 ? "d" : "", (id >> 2) & 1, (id >> 3) & 1, epi[(id >> 4) & 3],
              (id >> 6) & 1 ? "bf16" : "float", (id >> 7) & 1 ? "true" : "false");
     return ALS_OK;
   }
