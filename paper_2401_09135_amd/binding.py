@@ -12,7 +12,7 @@ VEC = dict(theta=0, momentum=1, delta=2, worker_theta=3, worker_start=4, adam_m=
 
 lib_path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libals.so")
 if not os.path.exists(lib_path):
-    raise ImportError(f"{lib_path} is missing: build it with `python -m paper_2401_09135_amd.build` "
+    raise ImportError(f"{lib_path} is missing: build it with `python paper_2401_09135_amd/build.py` "
                       "(there is no CPU fallback)")
 
 
