@@ -947,25 +947,20 @@ int gemm_mfma(const GemmDesc& g, hipStream_t st) {
   // 7/8 of the 512 resident slots (2 per CU).
   // The 256x256 kernel with two wavefront groups in alternating phases (buffering code 4; it
   // masks partial tiles, so M and N need only be multiples of 128) moves a third less operand data
-  // per flop than 256x128 and keeps the matrix pipes busy through its LDS traffic; it runs one
-  // workgroup per CU, so it needs enough tiles to fill the chip and enough K per tile to amortise
-  // a prologue and an epilogue that nothing overlaps.  Measured against the other variants on the
-  // 150M-class and 20M-class shapes (profiles/gemm_mfma_microbench.md): it wins from about 7/8 of a
-  // round of 256 tiles unless both K and the tile count are small; weight gradients (split along
-  // K) from a few dozen tiles.
+  // per flop than 256x128 and keeps the matrix pipes busy through its LDS traffic.  One product
+  // at a time on an idle chip, it loses to the smaller tiles when its tiles fill less than a
+  // round of CUs or K is very short (profiles/gemm_mfma_microbench.md); inside worker steps that
+  // overlap on several streams it wins there too (20M-class workload: +4 to +5 % tokens/s with
+  // it on every product, 150M-class: equal), so it is used whenever the product has at least one
+  // whole tile in each direction.  Its direct-to-LDS form (code 5) is 3-6 % faster in the
+  // microbenchmark and equal or slightly slower inside a step; the register-staged form is the
+  // default.
   int bm = 128, bn = 128, nbuf = 1;
-  const int t256 = ((g.M + 255) / 256) * ((g.N + 255) / 256);
-  const bool pp_pays = g.a_layout == 1 ? t256 >= 24
-                                       : t256 >= 224 && !(g.K < 768 && t256 < 1024);
+  const bool pp_pays = g.M >= 256 && g.N >= 256;
   if (g_force_bm && g_force_nbuf == 4) { bm = 256; bn = 256; nbuf = 4; }
   else if (g_force_bm && g_force_nbuf == 5) { bm = 256; bn = 256; nbuf = 5; }
   else if (g_force_bm && fits(g.M, g.N, g_force_bm, g_force_bn)) { bm = g_force_bm; bn = g_force_bn; nbuf = g_force_nbuf; }
-  // (inside a worker step, with operands that were written by another kernel moments before, the
-  // direct-to-LDS form and the register-staged form run within 1 % of each other; the direct form
-  // is a few per cent ahead on the input-gradient products, whose operands are both
-  // contraction-contiguous, and is used there)
-  else if (!g_force_bm && pp_pays)
-    { bm = 256; bn = 256; nbuf = g_force_nbuf ? g_force_nbuf : (g.a_layout == 0 && g.b_layout == 1 ? 5 : 4); }
+  else if (!g_force_bm && pp_pays) { bm = 256; bn = 256; nbuf = g_force_nbuf == 5 ? 5 : 4; }
   else if (g.a_layout == 1) {
     if (fits(g.M, g.N, 256, 256) && (g.M / 256) * (g.N / 256) >= 64) { bm = 256; bn = 256; nbuf = 2; }
     else if (fits(g.M, g.N, 256, 128) && (g.M / 256) * (g.N / 128) >= 128) { bm = 256; bn = 128; nbuf = 1; }
