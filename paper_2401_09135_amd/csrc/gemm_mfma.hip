@@ -24,6 +24,7 @@
 #include <hip/hip_ext.h>
 #include <stdio.h>
 
+#include <atomic>
 #include <mutex>
 #include <string>
 #include <vector>
@@ -99,7 +100,7 @@ __device__ __forceinline__ void gelu_both(float u, float& val, float& grad) {
 struct MfmaArgs {
   const bf16* A; const bf16* B;
   int64_t lda, ldb;
-  int M, N, K;      // K = length of this launch's K range per split
+  int M, N, K;      // K = whole contraction length (split-K: the kernel takes its share of the slices)
   int tiles_m, tiles_n, nsplit;
   void* C; int64_t ldc;
   const float* R; int64_t ldr;
@@ -238,7 +239,16 @@ __global__ __launch_bounds__(64 * tile_waves(BM, BN), OCC) void gemm_mfma_kernel
     tile = (id < per * 8) ? (id % 8) * per + id / 8 : id;
   }
   const int m0 = (tile / g.tiles_n) * BM, n0 = (tile % g.tiles_n) * BN;
-  const int64_t kbase = (int64_t)zsplit * g.K;
+  // split-K: the K slices are dealt to the splits as evenly as whole slices allow (the first
+  // nk_total % nsplit splits take one slice more)
+  const int nk_total = g.K / BK;
+  int nk = nk_total, slice0 = 0;
+  if (SPLIT) {
+    const int q = nk_total / g.nsplit, r = nk_total % g.nsplit;
+    nk = q + (zsplit < r ? 1 : 0);
+    slice0 = zsplit * q + (zsplit < r ? zsplit : r);
+  }
+  const int64_t kbase = (int64_t)slice0 * BK;
 
   // Global addressing: one 32-bit per-lane byte offset per operand; everything else (tile
   // origin, 16-byte chunk index, K slice) is uniform and lives in scalar registers, so a
@@ -350,7 +360,6 @@ __global__ __launch_bounds__(64 * tile_waves(BM, BN), OCC) void gemm_mfma_kernel
     }
   };
 
-  const int nk = g.K / BK;
   if (NBUF == 2) {
     load_global(0, ra[0], rb[0]);
     store_lds(0, ra[0], rb[0]);
@@ -449,8 +458,14 @@ __global__ __launch_bounds__(512, 1) void gemm_pp_kernel(MfmaArgs g) {
     tn = b * GN + r % width;
   }
   const int m0 = tm * BM, n0 = tn * BN;
-  const int64_t kbase = (int64_t)zsplit * g.K;
-  const int nk = g.K / BK;
+  const int nk_total = g.K / BK;   // split-K: slices dealt to the splits as evenly as whole slices allow
+  int nk = nk_total, slice0 = 0;
+  if (SPLIT) {
+    const int q = nk_total / g.nsplit, r = nk_total % g.nsplit;
+    nk = q + (zsplit < r ? 1 : 0);
+    slice0 = zsplit * q + (zsplit < r ? zsplit : r);
+  }
+  const int64_t kbase = (int64_t)slice0 * BK;
 
   // global addressing: scalar tile origin + per-lane, per-chunk 32-bit byte offsets (rows / column
   // runs beyond the matrix are clamped onto its last ones)
@@ -643,8 +658,14 @@ __global__ __launch_bounds__(512, 1) void gemm_ppd_kernel(MfmaArgs g) {
     tn = b * GN + r % width;
   }
   const int m0 = tm * BM, n0 = tn * BN;
-  const int64_t kbase = (int64_t)zsplit * g.K;
-  const int nk = g.K / BK;
+  const int nk_total = g.K / BK;   // split-K: slices dealt to the splits as evenly as whole slices allow
+  int nk = nk_total, slice0 = 0;
+  if (SPLIT) {
+    const int q = nk_total / g.nsplit, r = nk_total % g.nsplit;
+    nk = q + (zsplit < r ? 1 : 0);
+    slice0 = zsplit * q + (zsplit < r ? zsplit : r);
+  }
+  const int64_t kbase = (int64_t)slice0 * BK;
 
   // Wavefront w, instruction i (0..3) moves 1 KB of the A tile and 1 KB of the B tile: tile rows
   // 8 (4 w + i) .. + 7 (contraction-contiguous) or k rows 2 (4 w + i), + 1 (contraction-strided).
@@ -788,11 +809,11 @@ template <int BM, int BN, int AL, int BL, int EPI, typename TO, bool SPLIT, int 
 int launch(const MfmaArgs& a, int nsplit, hipStream_t st) {
   typedef Tile<BM, BN, AL, BL, NBUF> TL;
   auto kern = gemm_mfma_kernel<BM, BN, AL, BL, EPI, TO, SPLIT, NBUF, OCC>;
-  static bool attr_set = false;  // idempotent; a race only repeats the call
-  if (!attr_set) {
+  static std::atomic<bool> attr_set{false};  // the call is idempotent: a race only repeats it
+  if (!attr_set.load(std::memory_order_acquire)) {
     ALS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES));
-    attr_set = true;
+    attr_set.store(true, std::memory_order_release);
   }
   dim3 grid(a.tiles_m * a.tiles_n * nsplit);
   ProfRec rec;
@@ -814,7 +835,7 @@ int launch(const MfmaArgs& a, int nsplit, hipStream_t st) {
   ALS_CHECK_LAUNCH();
   if (prof) {
     rec.id = kernel_id(BM, BN, AL, BL, EPI, sizeof(TO) == 2, SPLIT, NBUF);
-    rec.flops = 2.0 * a.M * a.N * (double)a.K * nsplit;
+    rec.flops = 2.0 * a.M * a.N * (double)a.K;
     std::lock_guard<std::mutex> lk(g_prof_mu);
     g_prof.push_back(rec);
   }
@@ -825,11 +846,11 @@ template <int AL, int BL, int EPI, typename TO, bool SPLIT>
 int launch_pp(const MfmaArgs& a, int nsplit, hipStream_t st) {
   typedef Tile<256, 256, AL, BL, 2> TL;
   auto kern = gemm_pp_kernel<AL, BL, EPI, TO, SPLIT>;
-  static bool attr_set = false;  // idempotent; a race only repeats the call
-  if (!attr_set) {
+  static std::atomic<bool> attr_set{false};  // the call is idempotent: a race only repeats it
+  if (!attr_set.load(std::memory_order_acquire)) {
     ALS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES));
-    attr_set = true;
+    attr_set.store(true, std::memory_order_release);
   }
   dim3 grid(a.tiles_m * a.tiles_n * nsplit);
   ProfRec rec;
@@ -846,7 +867,7 @@ int launch_pp(const MfmaArgs& a, int nsplit, hipStream_t st) {
   ALS_CHECK_LAUNCH();
   if (prof) {
     rec.id = kernel_id(256, 256, AL, BL, EPI, sizeof(TO) == 2, SPLIT, 4);
-    rec.flops = 2.0 * a.M * a.N * (double)a.K * nsplit;
+    rec.flops = 2.0 * a.M * a.N * (double)a.K;
     std::lock_guard<std::mutex> lk(g_prof_mu);
     g_prof.push_back(rec);
   }
@@ -857,10 +878,10 @@ template <int AL, int BL, int EPI, typename TO, bool SPLIT>
 int launch_ppd(const MfmaArgs& a, int nsplit, hipStream_t st) {
   constexpr int LDS = 2 * (256 * 128 + 256 * 128);
   auto kern = gemm_ppd_kernel<AL, BL, EPI, TO, SPLIT>;
-  static bool attr_set = false;  // idempotent; a race only repeats the call
-  if (!attr_set) {
+  static std::atomic<bool> attr_set{false};  // the call is idempotent: a race only repeats it
+  if (!attr_set.load(std::memory_order_acquire)) {
     ALS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, LDS));
-    attr_set = true;
+    attr_set.store(true, std::memory_order_release);
   }
   dim3 grid(a.tiles_m * a.tiles_n * nsplit);
   ProfRec rec;
@@ -877,7 +898,7 @@ int launch_ppd(const MfmaArgs& a, int nsplit, hipStream_t st) {
   ALS_CHECK_LAUNCH();
   if (prof) {
     rec.id = kernel_id(256, 256, AL, BL, EPI, sizeof(TO) == 2, SPLIT, 4) | 1 << 10;   // bit 10: direct-to-LDS form
-    rec.flops = 2.0 * a.M * a.N * (double)a.K * nsplit;
+    rec.flops = 2.0 * a.M * a.N * (double)a.K;
     std::lock_guard<std::mutex> lk(g_prof_mu);
     g_prof.push_back(rec);
   }
@@ -936,7 +957,9 @@ static int dispatch(const GemmDesc& g, const MfmaArgs& a, int bm, int bn, int nb
   ALS_TILE_SWITCH(1, 0, EPI_STORE, float, false);
 }
 
-static int g_force_bm = 0, g_force_bn = 0, g_force_nbuf = 0;  // tuning override, 0 = automatic
+// tuning override, 0 = automatic (set by als_k_set_gemm_tile; atomics so that a launch on another
+// thread reads whole values, the three are still not changed as one)
+static std::atomic<int> g_force_bm{0}, g_force_bn{0}, g_force_nbuf{0};
 
 int gemm_mfma(const GemmDesc& g, hipStream_t st) {
   if (!gemm_mfma_supported(g)) return set_error(ALS_ERR_INVALID, "gemm_mfma: unsupported shape or layout");
@@ -979,7 +1002,8 @@ int gemm_mfma(const GemmDesc& g, hipStream_t st) {
     // and for 256x128, 3 per CU for the single-buffered 128x128 one).  Candidates are costed in
     // microseconds with measured rates: the product at 700 TFLOP/s times the round-up loss of
     // the last round, plus the fp32 partials written and read back at 4 TB/s; each split keeps
-    // at least 512 of K and the partials must fit the workspace.
+    // at least 512 of K and the partials must fit the workspace.  Splits need not be equal: the K
+    // slices are dealt out as evenly as whole slices allow.
     const size_t per = (size_t)g.M * g.N * sizeof(float);
     const int maxws = g.ws ? (int)(g.ws_bytes / per) : 1;
     const double t_prod = 2.0 * g.M * g.N * (double)g.K / 700e6;  // us
@@ -989,11 +1013,15 @@ int gemm_mfma(const GemmDesc& g, hipStream_t st) {
       const int nb = cand == 0 ? nbuf : (nbuf == 2 ? 1 : 2);
       const int slots = 256 * (bn == 256 ? 1 : (bm == 128 && nb == 1) ? 3 : 2);  // resident workgroups on the chip
       const int tiles = a.tiles_m * a.tiles_n;
+      const int nk_total = g.K / BK;
       for (int ns = 1; ns <= 64 && ns <= maxws; ns++) {
-        if (g.K % (ns * BK) || (ns > 1 && g.K / ns < 512)) continue;
+        const int s_wg = (nk_total + ns - 1) / ns;     // slices of the longest split
+        if (ns > 1 && s_wg < 8) continue;
         const int wgs = tiles * ns;
         const int rounds = (wgs + slots - 1) / slots;
-        double cost = t_prod * rounds * slots / wgs + (ns > 1 ? ns * (double)per * 2.0 / 4e6 : 0.0);
+        // a round lasts as long as its longest split; ideal = all slices spread over all slots
+        double cost = t_prod * ((double)rounds * s_wg * slots) / ((double)tiles * nk_total) +
+                      (ns > 1 ? ns * (double)per * 2.0 / 4e6 : 0.0);
         if (cand == 1) cost *= 1.03;  // prefer the first choice on near ties
         if (cost < best) { best = cost; best_nbuf = nb; best_ns = ns; }
       }
@@ -1002,7 +1030,7 @@ int gemm_mfma(const GemmDesc& g, hipStream_t st) {
     nsplit = best_ns;
   }
   if (nsplit > 1) {
-    a.K = g.K / nsplit; a.nsplit = nsplit;
+    a.nsplit = nsplit;
     a.C = g.ws; a.ldc = g.N; a.split_stride = (int64_t)g.M * g.N;
     int rc = dispatch(g, a, bm, bn, nbuf, nsplit, st);
     if (rc) return rc;

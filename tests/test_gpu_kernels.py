@@ -351,3 +351,62 @@ def test_gemm_mfma_tile_variants_agree():
             np.testing.assert_allclose(c.cpu().numpy(), ref, rtol=1e-4, atol=2e-3, err_msg=str(tile))
     finally:
         A.lib.als_k_set_gemm_tile(0, 0, 0)
+
+
+@pytest.mark.parametrize("tile", [(128, 128, 1), (128, 128, 2), (256, 256, 4), (256, 256, 5)])
+def test_gemm_epilogues_under_every_mfma_kernel(tile):
+    """Residual, GELU pair, multiply-by-saved-derivative and plain bf16 / fp32 stores under each MFMA
+    kernel (4 = the 256 x 256 kernel with two wavefront groups in alternating phases, 5 = its
+    direct-to-LDS form), on a shape whose last tiles are partial in both directions for the 256-wide
+    kernels (384 x 640) and whose K (192) is three slices."""
+    M, N, K = 384, 640, 192
+    rng = np.random.default_rng(7)
+    a = _dev(rng.standard_normal((M, K)).astype(np.float32), torch.bfloat16)
+    w = _dev(rng.standard_normal((K, N)).astype(np.float32) * 0.2, torch.bfloat16)
+    acc = a.float().cpu().numpy().astype(np.float64) @ w.float().cpu().numpy().astype(np.float64)
+    r = _dev(rng.standard_normal((M, N)).astype(np.float32))
+    u = _dev(rng.standard_normal((M, N)).astype(np.float32), torch.bfloat16)
+    wt = w.t().contiguous()
+    try:
+        A.lib.als_k_set_gemm_tile(*tile)
+        c = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
+        A.k_gemm_ex(a, w, c, M, N, K, 0, 0, True, epi=1, R=r)
+        gp = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=DEV)
+        gv = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=DEV)
+        A.k_gemm_ex(a, w, gp, M, N, K, 0, 0, True, epi=2, C2=gv)
+        d = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=DEV)
+        A.k_gemm_ex(a, wt, d, M, N, K, 0, 1, True, epi=3, U=u)
+        pb = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=DEV)
+        A.k_gemm(a, w, pb, M, N, K, 0, 0, use_mfma=True)
+        pf = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
+        A.k_gemm(a, wt, pf, M, N, K, 0, 1, use_mfma=True)
+        torch.cuda.synchronize()
+    finally:
+        A.lib.als_k_set_gemm_tile(0, 0, 0)
+    np.testing.assert_allclose(c.cpu().numpy(), acc + r.cpu().numpy(), rtol=1e-4, atol=1e-3)
+    np.testing.assert_allclose(gv.float().cpu().numpy(), lm.gelu_fwd(acc), rtol=1e-2, atol=1e-2)
+    np.testing.assert_allclose(gp.float().cpu().numpy(), lm.gelu_grad(acc), rtol=1e-2, atol=1e-2)
+    np.testing.assert_allclose(d.float().cpu().numpy(), acc * u.float().cpu().numpy(), rtol=1e-2, atol=2e-2)
+    np.testing.assert_allclose(pb.float().cpu().numpy(), acc, rtol=1e-2, atol=1e-2)
+    np.testing.assert_allclose(pf.cpu().numpy(), acc, rtol=1e-4, atol=1e-3)
+
+
+@pytest.mark.parametrize("tile", [(256, 256, 4), (256, 256, 5)])
+@pytest.mark.parametrize("M,N,K,scratch", [(256, 256, 64, 0), (384, 896, 4096, 8), (896, 2688, 16384, 6), (128, 512, 1024, 4)])
+def test_pingpong_gemm_weight_gradient_shapes(tile, M, N, K, scratch):
+    """The 256 x 256 kernels on the weight-gradient layout (both operands contraction-strided): a
+    single K slice, partial tiles in both directions, split along K when scratch for the partials
+    is given, and a product with fewer rows than a tile."""
+    rng = np.random.default_rng(M + N + K)
+    x = _dev(rng.standard_normal((K, M)).astype(np.float32), torch.bfloat16)
+    dy = _dev(rng.standard_normal((K, N)).astype(np.float32), torch.bfloat16)
+    ref = x.float().cpu().numpy().astype(np.float64).T @ dy.float().cpu().numpy().astype(np.float64)
+    ws = torch.empty(scratch * M * N, dtype=torch.float32, device=DEV) if scratch else None
+    c = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
+    try:
+        A.lib.als_k_set_gemm_tile(*tile)
+        A.k_gemm(x, dy, c, M, N, K, 1, 0, use_mfma=True, ws=ws)
+        torch.cuda.synchronize()
+    finally:
+        A.lib.als_k_set_gemm_tile(0, 0, 0)
+    np.testing.assert_allclose(c.cpu().numpy(), ref, rtol=1e-4, atol=2e-3 * np.sqrt(K / 64))
