@@ -25,7 +25,23 @@
 //   p = 4 kt + 4.  The global loads of a chunk are issued right after the chunk's registers were
 //   stored, a whole slice (four phases) before they are needed.
 // Rows / columns beyond M / N (M, N multiples of 128, not of 256) are loaded from clamped
-// addresses, multiplied, and not stored: a wavefront's 128 x 64 sub-tile is wholly inside or outside.
+// addresses and not stored.  A wavefront's 128 x 64 sub-tile is wholly inside or outside the matrix;
+// a wavefront outside reads no fragments and issues no MFMAs, and the sub-tiles are dealt to the
+// groups (sub_tile below) so that a dead half of the tile is one whole group.
+// Which 128 x 64 sub-tile of the 256 x 256 tile a wavefront owns: row half mh, column quarter nq.
+// Normally group g (wavefronts 4 g .. 4 g + 3) owns columns 128 g .. 128 g + 127.  In a tile whose
+// lower 128 rows lie outside the matrix while its columns do not, the groups own the row halves
+// instead: the dead half is then ONE group, whose compute phases are empty, and a K slice of that
+// tile costs two MFMA phases instead of four (a dead column half is one group in the normal map).
+// Every (mh, nq) pair has exactly one wavefront in both maps, and the four wavefronts of a group sit
+// on the four SIMDs either way.
+struct SubTile { int mh, nq; };
+__device__ __forceinline__ SubTile sub_tile(int wave, int m0, int n0, int M, int N) {
+  const int grp = wave >> 2, sub = wave & 3;
+  const bool by_rows = m0 + 128 >= M && n0 + 128 < N;   // workgroup-uniform
+  return by_rows ? SubTile{grp, sub} : SubTile{sub >> 1, grp * 2 + (sub & 1)};
+}
+
 template <int AL, int BL, int EPI, typename TO, bool SPLIT>
 __global__ __launch_bounds__(512, 1) void gemm_pp_kernel(MfmaArgs g) {
   constexpr int BM = 256, BN = 256;
@@ -34,8 +50,7 @@ __global__ __launch_bounds__(512, 1) void gemm_pp_kernel(MfmaArgs g) {
   constexpr int WM = 128, WN = 64, TM = 4, TN = 2;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int grp = wave >> 2, wm = (wave >> 1) & 1, wn = wave & 1;
-  const int ncol0 = grp * 128 + wn * WN;   // this wavefront's first column inside the tile
+  const int grp = wave >> 2;
 
   int ntiles = g.tiles_m * g.tiles_n;
   int id = blockIdx.x, tile, zsplit = 0;
@@ -58,6 +73,8 @@ __global__ __launch_bounds__(512, 1) void gemm_pp_kernel(MfmaArgs g) {
     tn = b * GN + r % width;
   }
   const int m0 = tm * BM, n0 = tn * BN;
+  const SubTile st = sub_tile(wave, m0, n0, g.M, g.N);
+  const int mh = st.mh, ncol0 = st.nq * WN;   // this wavefront's row half and first column inside the tile
   const int nk_total = g.K / BK;   // split-K: slices dealt to the splits as evenly as whole slices allow
   int nk = nk_total, slice0 = 0;
   if (SPLIT) {
@@ -134,27 +151,33 @@ __global__ __launch_bounds__(512, 1) void gemm_pp_kernel(MfmaArgs g) {
       for (int v = 0; v < 16; v++) acc[i][j][v] = 0.0f;
 
   int a_off, b_off;
-  if (AL == 0) a_off = (wm * WM + (lane & 31)) * TL::A_STRIDE + (lane >> 5) * 16;
-  else a_off = ((lane >> 5) * 8 + ((lane & 15) >> 2)) * TL::A_STRIDE + (wm * WM + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;
+  if (AL == 0) a_off = (mh * WM + (lane & 31)) * TL::A_STRIDE + (lane >> 5) * 16;
+  else a_off = ((lane >> 5) * 8 + ((lane & 15) >> 2)) * TL::A_STRIDE + (mh * WM + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;
   if (BL == 1) b_off = (ncol0 + (lane & 31)) * TL::B_STRIDE + (lane >> 5) * 16;
   else b_off = ((lane >> 5) * 8 + ((lane & 15) >> 2)) * TL::B_STRIDE + (ncol0 + ((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;
 
+  // A wavefront whose 128 x 64 sub-tile lies outside the matrix (M, N multiples of 128, not of 256)
+  // still moves its share of the operand tiles and keeps the barriers, but reads no fragments and
+  // issues no MFMAs: the SIMD's matrix pipe and the LDS are left to the live wavefronts.
+  const bool live = m0 + mh * WM < g.M && n0 + ncol0 < g.N;   // wavefront-uniform
   bf16x8 af[2][TM], bfr[2][TN];   // fragments of one 32-wide half of a K slice
   auto memory_phase = [&](int kt, int h) {
     const char* As = smem + (kt & 1) * TL::STAGE;
     const char* Bs = As + TL::A_BYTES;
+    if (live) {
 #pragma unroll
-    for (int s2 = 0; s2 < 2; s2++) {
-      const int kk = 2 * h + s2;
+      for (int s2 = 0; s2 < 2; s2++) {
+        const int kk = 2 * h + s2;
 #pragma unroll
-      for (int j = 0; j < TN; j++) {
-        if (BL == 1) bfr[s2][j] = lds_read_direct(Bs + b_off + j * 32 * TL::B_STRIDE + kk * 32);
-        else bfr[s2][j] = lds_read_tr(Bs + b_off + kk * 16 * TL::B_STRIDE + j * 64, TL::B_STRIDE);
-      }
+        for (int j = 0; j < TN; j++) {
+          if (BL == 1) bfr[s2][j] = lds_read_direct(Bs + b_off + j * 32 * TL::B_STRIDE + kk * 32);
+          else bfr[s2][j] = lds_read_tr(Bs + b_off + kk * 16 * TL::B_STRIDE + j * 64, TL::B_STRIDE);
+        }
 #pragma unroll
-      for (int i = 0; i < TM; i++) {
-        if (AL == 0) af[s2][i] = lds_read_direct(As + a_off + i * 32 * TL::A_STRIDE + kk * 32);
-        else af[s2][i] = lds_read_tr(As + a_off + kk * 16 * TL::A_STRIDE + i * 64, TL::A_STRIDE);
+        for (int i = 0; i < TM; i++) {
+          if (AL == 0) af[s2][i] = lds_read_direct(As + a_off + i * 32 * TL::A_STRIDE + kk * 32);
+          else af[s2][i] = lds_read_tr(As + a_off + kk * 16 * TL::A_STRIDE + i * 64, TL::A_STRIDE);
+        }
       }
     }
     if (kt + 1 < nk) {
@@ -167,15 +190,17 @@ __global__ __launch_bounds__(512, 1) void gemm_pp_kernel(MfmaArgs g) {
   };
   auto compute_phase = [&]() {
     __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_setprio(1);
+    if (live) {
+      __builtin_amdgcn_s_setprio(1);
 #pragma unroll
-    for (int s2 = 0; s2 < 2; s2++)
+      for (int s2 = 0; s2 < 2; s2++)
 #pragma unroll
-      for (int i = 0; i < TM; i++)
+        for (int i = 0; i < TM; i++)
 #pragma unroll
-        for (int j = 0; j < TN; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[s2][j], af[s2][i], acc[i][j], 0, 0, 0);
-    __builtin_amdgcn_s_setprio(0);
+          for (int j = 0; j < TN; j++)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[s2][j], af[s2][i], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_s_setprio(0);
+    }
     __builtin_amdgcn_sched_barrier(0);
   };
 
@@ -201,12 +226,12 @@ __global__ __launch_bounds__(512, 1) void gemm_pp_kernel(MfmaArgs g) {
     }
   }
 
-  if (m0 + wm * WM >= g.M || n0 + ncol0 >= g.N) return;   // sub-tile outside the matrix
+  if (!live) return;   // sub-tile outside the matrix
   TO* C = reinterpret_cast<TO*>(g.C);
   if (SPLIT) C += (int64_t)zsplit * g.split_stride;
   typedef WaveEpilogue<TM, TN, WN, EPI, TO> EP;
   static_assert(8 * 32 * EP::PITCH <= TL::LDS_BYTES, "epilogue staging must fit the operand buffers");
-  EP ep(g, lane, m0 + wm * WM, n0 + ncol0);
+  EP ep(g, lane, m0 + mh * WM, n0 + ncol0);
   ep.preload();
   ep.run(acc, smem + wave * (32 * EP::PITCH), C);
 }
@@ -237,8 +262,7 @@ __global__ __launch_bounds__(512, 1) void gemm_ppd_kernel(MfmaArgs g) {
   constexpr int WM = 128, WN = 64, TM = 4, TN = 2;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int grp = wave >> 2, wm = (wave >> 1) & 1, wn = wave & 1;
-  const int ncol0 = grp * 128 + wn * WN;
+  const int grp = wave >> 2;
 
   int ntiles = g.tiles_m * g.tiles_n;
   int id = blockIdx.x, tile, zsplit = 0;
@@ -258,6 +282,8 @@ __global__ __launch_bounds__(512, 1) void gemm_ppd_kernel(MfmaArgs g) {
     tn = b * GN + r % width;
   }
   const int m0 = tm * BM, n0 = tn * BN;
+  const SubTile st = sub_tile(wave, m0, n0, g.M, g.N);
+  const int mh = st.mh, nq = st.nq, ncol0 = nq * WN;
   const int nk_total = g.K / BK;   // split-K: slices dealt to the splits as evenly as whole slices allow
   int nk = nk_total, slice0 = 0;
   if (SPLIT) {
@@ -320,40 +346,45 @@ __global__ __launch_bounds__(512, 1) void gemm_ppd_kernel(MfmaArgs g) {
   const int fx = ((lane >> 5) ^ (((lane & 31) >> 1) & 7));
   const int tx = (lane >> 2) & 3;
   const int tr_row = ((lane >> 5) * 8 + ((lane & 15) >> 2)) * 512 + ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
-  const int a_off = AL == 0 ? (wm * WM + (lane & 31)) * 128 : tr_row + wm * 256;
-  const int b_off = BL == 1 ? (ncol0 + (lane & 31)) * 128 : tr_row + grp * 256;
+  const int a_off = AL == 0 ? (mh * WM + (lane & 31)) * 128 : tr_row + mh * 256;
+  const int b_off = BL == 1 ? (ncol0 + (lane & 31)) * 128 : tr_row + (nq >> 1) * 256;
+  const bool live = m0 + mh * WM < g.M && n0 + ncol0 < g.N;   // as in gemm_pp_kernel
   bf16x8 af[2][TM], bfr[2][TN];
   auto memory_phase = [&](int kt, int h) {
     const char* As = smem + (kt & 1) * STAGE;
     const char* Bs = As + A_BYTES;
+    if (live) {
 #pragma unroll
-    for (int s2 = 0; s2 < 2; s2++) {
-      const int kk = 2 * h + s2;
-      const int pos = ((kk * 2) ^ fx) * 16;
+      for (int s2 = 0; s2 < 2; s2++) {
+        const int kk = 2 * h + s2;
+        const int pos = ((kk * 2) ^ fx) * 16;
 #pragma unroll
-      for (int j = 0; j < TN; j++) {
-        if (BL == 1) bfr[s2][j] = lds_read_direct(Bs + b_off + j * 32 * 128 + pos);
-        else bfr[s2][j] = lds_read_tr(Bs + b_off + kk * 16 * 512 + (((wn * 2 + j) ^ tx) << 6), 512);
-      }
+        for (int j = 0; j < TN; j++) {
+          if (BL == 1) bfr[s2][j] = lds_read_direct(Bs + b_off + j * 32 * 128 + pos);
+          else bfr[s2][j] = lds_read_tr(Bs + b_off + kk * 16 * 512 + ((((nq & 1) * 2 + j) ^ tx) << 6), 512);
+        }
 #pragma unroll
-      for (int i = 0; i < TM; i++) {
-        if (AL == 0) af[s2][i] = lds_read_direct(As + a_off + i * 32 * 128 + pos);
-        else af[s2][i] = lds_read_tr(As + a_off + kk * 16 * 512 + ((i ^ tx) << 6), 512);
+        for (int i = 0; i < TM; i++) {
+          if (AL == 0) af[s2][i] = lds_read_direct(As + a_off + i * 32 * 128 + pos);
+          else af[s2][i] = lds_read_tr(As + a_off + kk * 16 * 512 + ((i ^ tx) << 6), 512);
+        }
       }
     }
     if (h == 0 && kt + 1 < nk) issue_loads(kt + 1);
   };
   auto compute_phase = [&]() {
     __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_setprio(1);
+    if (live) {
+      __builtin_amdgcn_s_setprio(1);
 #pragma unroll
-    for (int s2 = 0; s2 < 2; s2++)
+      for (int s2 = 0; s2 < 2; s2++)
 #pragma unroll
-      for (int i = 0; i < TM; i++)
+        for (int i = 0; i < TM; i++)
 #pragma unroll
-        for (int j = 0; j < TN; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[s2][j], af[s2][i], acc[i][j], 0, 0, 0);
-    __builtin_amdgcn_s_setprio(0);
+          for (int j = 0; j < TN; j++)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[s2][j], af[s2][i], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_s_setprio(0);
+    }
     __builtin_amdgcn_sched_barrier(0);
   };
 
@@ -376,12 +407,12 @@ __global__ __launch_bounds__(512, 1) void gemm_ppd_kernel(MfmaArgs g) {
     }
   }
 
-  if (m0 + wm * WM >= g.M || n0 + ncol0 >= g.N) return;   // sub-tile outside the matrix
+  if (!live) return;   // sub-tile outside the matrix
   TO* C = reinterpret_cast<TO*>(g.C);
   if (SPLIT) C += (int64_t)zsplit * g.split_stride;
   typedef WaveEpilogue<TM, TN, WN, EPI, TO> EP;
   static_assert(8 * 32 * EP::PITCH <= LDS_BYTES, "epilogue staging must fit the operand buffers");
-  EP ep(g, lane, m0 + wm * WM, n0 + ncol0);
+  EP ep(g, lane, m0 + mh * WM, n0 + ncol0);
   ep.preload();
   ep.run(acc, smem + wave * (32 * EP::PITCH), C);
 }
