@@ -410,3 +410,30 @@ def test_pingpong_gemm_weight_gradient_shapes(tile, M, N, K, scratch):
     finally:
         A.lib.als_k_set_gemm_tile(0, 0, 0)
     np.testing.assert_allclose(c.cpu().numpy(), ref, rtol=1e-4, atol=2e-3 * np.sqrt(K / 64))
+
+
+@pytest.mark.parametrize("tile", [(256, 256, 4), (256, 256, 5)])
+@pytest.mark.parametrize("layout", [(0, 0), (0, 1), (1, 0)])
+@pytest.mark.parametrize("M,N", [(384, 512), (128, 256), (512, 384), (384, 384), (896, 896)])
+def test_pingpong_gemm_half_tiles(tile, layout, M, N):
+    """Half tiles of the 256 x 256 kernels: a dead lower row half (the wavefront groups then own the
+    row halves), a dead right column half, and the corner tile with both, in every operand layout;
+    dead wavefronts multiply nothing and every live element is exact to fp32 accumulation."""
+    al, bl = layout
+    K = 320
+    rng = np.random.default_rng([M, N, al, bl])
+    a = rng.standard_normal((M, K)).astype(np.float32)
+    b = rng.standard_normal((K, N)).astype(np.float32)
+    ad = _dev(a if al == 0 else a.T.copy(), torch.bfloat16)
+    bd = _dev(b if bl == 0 else b.T.copy(), torch.bfloat16)
+    ar = ad.float().cpu().numpy().astype(np.float64)
+    br = bd.float().cpu().numpy().astype(np.float64)
+    ref = (ar if al == 0 else ar.T) @ (br if bl == 0 else br.T)
+    c = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
+    try:
+        A.lib.als_k_set_gemm_tile(*tile)
+        A.k_gemm(ad, bd, c, M, N, K, al, bl, use_mfma=True)
+        torch.cuda.synchronize()
+    finally:
+        A.lib.als_k_set_gemm_tile(0, 0, 0)
+    np.testing.assert_allclose(c.cpu().numpy(), ref, rtol=1e-4, atol=4e-3)
