@@ -71,7 +71,9 @@ struct MfmaArgs {
 // whole row segments, 16 bytes per lane: every global access of the epilogue (residual and
 // saved-derivative reads, outputs) is then fully coalesced.  (Storing straight from the
 // accumulator layout gives 8- or 16-byte pieces in 32 different rows per instruction; measured
-// 8 % slower on the whole step.)
+// 8 % slower on the whole step.)  Outputs are written with non-temporal stores: a round of tiles
+// writes 32-64 MB at once, as much as all L2s hold, and no tile reads them back (3-5 % on the
+// products with short K, one product at a time).
 template <int TM, int TN, int WN, int EPI, typename TO>
 struct WaveEpilogue {
   static constexpr int PITCH = WN * 4 + 16;  // rows 4 banks apart: 16-byte accesses of 16 rows, or of two row halves, never collide
@@ -145,7 +147,7 @@ struct WaveEpilogue {
         }
         if (sizeof(TO) == 4) {
           f32x4 o = {x[0], x[1], x[2], x[3]};
-          *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(C) + ci) = o;
+          __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(reinterpret_cast<float*>(C) + ci));
         } else {
           bf16x8 o;
           if (EPI == EPI_GELU) {  // C <- gelu'(acc), C2 <- gelu(acc)
@@ -157,12 +159,12 @@ struct WaveEpilogue {
               o[e & 7] = (bf16)grad;
               o2[e & 7] = (bf16)val;
             }
-            *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16*>(g.C2) + ci) = o2;
+            __builtin_nontemporal_store(__builtin_bit_cast(u32x4, o2), reinterpret_cast<u32x4*>(reinterpret_cast<bf16*>(g.C2) + ci));
           } else {
 #pragma unroll
             for (int e = 0; e < CPL; e++) o[e & 7] = (bf16)x[e];
           }
-          *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16*>(C) + ci) = o;
+          __builtin_nontemporal_store(__builtin_bit_cast(u32x4, o), reinterpret_cast<u32x4*>(reinterpret_cast<bf16*>(C) + ci));
         }
       }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // reads done before the next block overwrites
