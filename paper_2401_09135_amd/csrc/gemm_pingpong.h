@@ -28,6 +28,36 @@
 // addresses and not stored.  A wavefront's 128 x 64 sub-tile is wholly inside or outside the matrix;
 // a wavefront outside reads no fragments and issues no MFMAs, and the sub-tiles are dealt to the
 // groups (sub_tile below) so that a dead half of the tile is one whole group.
+// Workgroup id -> (tile row, tile column, K split).  Workgroup ids are dealt round-robin to the 8
+// XCDs, each with its own L2, so what matters is which work items share an XCD.
+//   No split: XCD x takes a contiguous run of tiles, numbered down column blocks 8 tiles wide, so
+//   that the 32 tiles it works on at a time form a 4 x 8 patch sharing 4 A panels and 8 B panels in
+//   its L2 (a row of 32 tiles would share one A panel and stream 32 B panels through it).
+//   Split-K: the (split, tile) pairs are ordered split-major, then along the LONGER tile direction,
+//   the shorter one fastest, and XCD x takes a contiguous run of them: the tiles it holds at a time
+//   share one K range and span the short direction completely, so the panels of the short
+//   direction are fetched by the few XCDs that hold that split and the panels of the long direction
+//   once each (dealing splits and tiles out by id alone makes every XCD fetch most of both operands).
+struct WorkItem { int tm, tn, zsplit; };
+template <bool SPLIT>
+__device__ __forceinline__ WorkItem work_item(int id, int tiles_m, int tiles_n, int nsplit) {
+  const int ntiles = tiles_m * tiles_n;
+  if (SPLIT) {
+    const int total = ntiles * nsplit, base = total / 8, rem = total % 8;
+    const int x = id & 7, j = id >> 3;
+    const int p = x * base + (x < rem ? x : rem) + j;   // XCD x holds ids x, x + 8, ...: base (+ 1) of them
+    const int z = p / ntiles, t = p - z * ntiles;
+    if (tiles_m <= tiles_n) return {t % tiles_m, t / tiles_m, z};
+    return {t / tiles_n, t % tiles_n, z};
+  }
+  const int per = ntiles / 8;
+  const int tile = (id < per * 8) ? (id % 8) * per + id / 8 : id;
+  constexpr int GN = 8;
+  const int span = GN * tiles_m, b = tile / span, r = tile - b * span;
+  const int width = tiles_n - b * GN < GN ? tiles_n - b * GN : GN;
+  return {r / width, b * GN + r % width, 0};
+}
+
 // Which 128 x 64 sub-tile of the 256 x 256 tile a wavefront owns: row half mh, column quarter nq.
 // Normally group g (wavefronts 4 g .. 4 g + 3) owns columns 128 g .. 128 g + 127.  In a tile whose
 // lower 128 rows lie outside the matrix while its columns do not, the groups own the row halves
@@ -52,27 +82,9 @@ __global__ __launch_bounds__(512, 1) void gemm_pp_kernel(MfmaArgs g) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int grp = wave >> 2;
 
-  int ntiles = g.tiles_m * g.tiles_n;
-  int id = blockIdx.x, tile, zsplit = 0;
-  if (SPLIT) {
-    zsplit = id % g.nsplit;
-    tile = id / g.nsplit;
-  } else {
-    int per = ntiles / 8;
-    tile = (id < per * 8) ? (id % 8) * per + id / 8 : id;
-  }
-  // Tiles are numbered down column blocks 8 tiles wide, so that the 32 tiles an XCD works on at
-  // a time form a 4 x 8 patch sharing 4 A panels and 8 B panels in its L2 (a row of 32 tiles would
-  // share one A panel and stream 32 B panels through it).
-  int tm, tn;
-  {
-    constexpr int GN = 8;
-    const int span = GN * g.tiles_m, b = tile / span, r = tile - b * span;
-    const int width = g.tiles_n - b * GN < GN ? g.tiles_n - b * GN : GN;
-    tm = r / width;
-    tn = b * GN + r % width;
-  }
-  const int m0 = tm * BM, n0 = tn * BN;
+  const WorkItem wi = work_item<SPLIT>(blockIdx.x, g.tiles_m, g.tiles_n, g.nsplit);
+  const int zsplit = wi.zsplit;
+  const int m0 = wi.tm * BM, n0 = wi.tn * BN;
   const SubTile st = sub_tile(wave, m0, n0, g.M, g.N);
   const int mh = st.mh, ncol0 = st.nq * WN;   // this wavefront's row half and first column inside the tile
   const int nk_total = g.K / BK;   // split-K: slices dealt to the splits as evenly as whole slices allow
@@ -264,24 +276,9 @@ __global__ __launch_bounds__(512, 1) void gemm_ppd_kernel(MfmaArgs g) {
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int grp = wave >> 2;
 
-  int ntiles = g.tiles_m * g.tiles_n;
-  int id = blockIdx.x, tile, zsplit = 0;
-  if (SPLIT) {
-    zsplit = id % g.nsplit;
-    tile = id / g.nsplit;
-  } else {
-    int per = ntiles / 8;
-    tile = (id < per * 8) ? (id % 8) * per + id / 8 : id;
-  }
-  int tm, tn;
-  {
-    constexpr int GN = 8;
-    const int span = GN * g.tiles_m, b = tile / span, r = tile - b * span;
-    const int width = g.tiles_n - b * GN < GN ? g.tiles_n - b * GN : GN;
-    tm = r / width;
-    tn = b * GN + r % width;
-  }
-  const int m0 = tm * BM, n0 = tn * BN;
+  const WorkItem wi = work_item<SPLIT>(blockIdx.x, g.tiles_m, g.tiles_n, g.nsplit);
+  const int zsplit = wi.zsplit;
+  const int m0 = wi.tm * BM, n0 = wi.tn * BN;
   const SubTile st = sub_tile(wave, m0, n0, g.M, g.N);
   const int mh = st.mh, nq = st.nq, ncol0 = nq * WN;
   const int nk_total = g.K / BK;   // split-K: slices dealt to the splits as evenly as whole slices allow
