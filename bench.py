@@ -38,7 +38,7 @@ HEADLINE = "lm150m"
 # comparison with the algorithmic bytes).  Counters cannot be collected from inside this process, so
 # the figure is carried here, keyed by workload and kernel; a kernel without an entry reports null.
 MEASURED_TRAFFIC_BYTES = {"lm20m": {"gemm_mfma_kernel<128, 128, 1, 0, STORE, float, true, 2, 2>": 99.0e6},
-                          "lm150m": {"gemm_pp_kernel<1, 0, STORE, float, true>": 212.0e6}}
+                          "lm150m": {"gemm_pp_kernel<1, 0, STORE, float, true>": 211.9e6}}
 
 
 def flops_per_token(w):
