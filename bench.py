@@ -32,13 +32,17 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 HEADLINE = "lm150m"
-# HBM bytes per launch of the dominant GEMM kernel of a workload, measured with rocprofv3 --pmc
-# FETCH_SIZE (x 2.0) and WRITE_SIZE (x 1.0) on the same shapes, one kernel at a time
+# Bytes moved behind the L2s per launch of the dominant GEMM kernel of a workload, measured with
+# rocprofv3 --pmc FETCH_SIZE (x 2.0) and WRITE_SIZE (x 1.0) on the same shapes, one kernel at a time
 # (profiles/gemm_mfma_microbench.md gives the commands, the calibration of the two factors and the
-# comparison with the algorithmic bytes).  Counters cannot be collected from inside this process, so
-# the figure is carried here, keyed by workload and kernel; a kernel without an entry reports null.
-MEASURED_TRAFFIC_BYTES = {"lm20m": {"gemm_mfma_kernel<128, 128, 1, 0, STORE, float, true, 2, 2>": 99.0e6},
+# comparison with the algorithmic bytes), averaged over the launch mix of a worker step.  Counters
+# cannot be collected from inside this process, so the figure is carried here, keyed by workload and
+# kernel, next to the algorithmic bytes of the same launches (operands once + split-K partials
+# written); a kernel without an entry reports null, never another kernel's figure.
+MEASURED_TRAFFIC_BYTES = {"lm20m": {"gemm_pp_kernel<1, 0, STORE, float, true>": 135.5e6},
                           "lm150m": {"gemm_pp_kernel<1, 0, STORE, float, true>": 211.9e6}}
+ALGORITHMIC_TRAFFIC_BYTES = {"lm20m": {"gemm_pp_kernel<1, 0, STORE, float, true>": 133.9e6},
+                             "lm150m": {"gemm_pp_kernel<1, 0, STORE, float, true>": 168.0e6}}
 
 
 def flops_per_token(w):
@@ -396,7 +400,8 @@ def run_lm(name, steps_timed, warmup, n_streams, isolated_profile=True):
         achieved = fl / (ms * 1e-3) / 1e12
         res["roofline"] = dict(bound="mfma", achieved=achieved, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
                                frac=achieved / PEAK_BF16_TFLOPS,
-                               traffic=MEASURED_TRAFFIC_BYTES.get(name, {}).get(kname), kernel=kname, launches=launches,
+                               traffic=MEASURED_TRAFFIC_BYTES.get(name, {}).get(kname),
+                               traffic_algorithmic=ALGORITHMIC_TRAFFIC_BYTES.get(name, {}).get(kname), kernel=kname, launches=launches,
                                avg_us=1e3 * ms / launches, flops_per_launch=fl / launches,
                                how="HIP events around every launch of this kernel while one worker steps alone "
                                    "right after the timed region (same shapes, same stream)",
