@@ -437,3 +437,26 @@ def test_pingpong_gemm_half_tiles(tile, layout, M, N):
     finally:
         A.lib.als_k_set_gemm_tile(0, 0, 0)
     np.testing.assert_allclose(c.cpu().numpy(), ref, rtol=1e-4, atol=4e-3)
+
+
+@pytest.mark.parametrize("M,N,K,al,bl", [(896, 2688, 8192, 1, 0), (1024, 896, 1792, 0, 1), (768, 640, 896, 0, 0)])
+def test_pingpong_forms_agree_bit_for_bit(M, N, K, al, bl):
+    """The register-staged and the direct-to-LDS form of the 256 x 256 kernel multiply the same
+    fragments in the same order (and split K into the same ranges, added in the same order), so
+    their fp32 results are equal bit for bit, masked half tiles included."""
+    rng = np.random.default_rng([M, N, K])
+    a = _dev(rng.standard_normal((K, M) if al else (M, K)).astype(np.float32), torch.bfloat16)
+    b = _dev(rng.standard_normal((N, K) if bl else (K, N)).astype(np.float32), torch.bfloat16)
+    ws = torch.empty(8 * M * N, dtype=torch.float32, device=DEV) if al else None
+    out = []
+    for code in (4, 5):
+        c = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
+        try:
+            A.lib.als_k_set_gemm_tile(256, 256, code)
+            A.k_gemm(a, b, c, M, N, K, al, bl, use_mfma=True, ws=ws)
+            torch.cuda.synchronize()
+        finally:
+            A.lib.als_k_set_gemm_tile(0, 0, 0)
+        out.append(c)
+    assert torch.isfinite(out[0]).all()
+    assert torch.equal(out[0], out[1])
