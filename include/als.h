@@ -228,6 +228,18 @@ int als_k_gemm(const void* A, const void* B, void* C, int M, int N, int K, int a
 int als_k_gemm_ex(const void* A, const void* B, void* C, int M, int N, int K, int a_layout,
                   int b_layout, int in_dtype, int out_dtype, int use_mfma, int epi, const float* R,
                   void* C2, const void* U, void* ws_dev, size_t ws_bytes, void* stream);
+/* All n weight gradients C_i = X_i^T dY_i of a backward pass (Alg. 1, inner step: the gradient of
+ * every weight matrix is a product over the batch's K tokens) as ONE launch of the MFMA kernel:
+ * X_i is [K, M_i] and dY_i [K, N_i], both bf16 row-major, C_i [M_i, N_i] fp32; M_i, N_i multiples of
+ * 128, K of 64, pointers 16-byte aligned.  Whole rounds of 256 x 256 tiles run over the full K and
+ * write C_i directly; the tiles of the last partial round are split along K into partial tiles that
+ * are added in a fixed order, so results do not depend on timing.  ws_dev: device scratch (256-byte
+ * aligned) of at least als_k_gemm_dw_grouped_ws_bytes(n, M, N) bytes (tables and partial tiles);
+ * the call uploads its tables and waits for that upload on the stream before it launches.
+ * Errors (ALS_ERR_INVALID): null pointers, unsupported shapes, workspace too small. */
+size_t als_k_gemm_dw_grouped_ws_bytes(int n, const int* M, const int* N);
+int als_k_gemm_dw_grouped(int n, const void* const* X, const void* const* dY, float* const* C,
+                          const int* M, const int* N, int K, void* ws_dev, size_t ws_bytes, void* stream);
 /* For callers that cannot allocate device memory and have no workspace to lend (code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc): als_k_gemm on the MFMA
  * path (bf16 operands, M, N multiples of 128, K of 64) with the split-K partials of the

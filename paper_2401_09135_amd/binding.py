@@ -341,6 +341,28 @@ def k_gemm_static_ws(A, B, C_out, M, N, K, a_layout=1, b_layout=0, stream=None):
                                     _dt(C_out), _stream_handle(stream)))
 
 
+lib.als_k_gemm_dw_grouped_ws_bytes.argtypes = [C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]
+lib.als_k_gemm_dw_grouped_ws_bytes.restype = C.c_size_t
+lib.als_k_gemm_dw_grouped.argtypes = [C.c_int, C.POINTER(_P), C.POINTER(_P), C.POINTER(_P), C.POINTER(C.c_int),
+                                      C.POINTER(C.c_int), C.c_int, _P, C.c_size_t, _P]
+
+
+def k_gemm_dw_grouped_ws_bytes(Ms, Ns) -> int:
+    n = len(Ms)
+    return int(lib.als_k_gemm_dw_grouped_ws_bytes(n, (C.c_int * n)(*Ms), (C.c_int * n)(*Ns)))
+
+
+def k_gemm_dw_grouped(Xs, dYs, Cs, K, ws, stream=None):
+    """als_k_gemm_dw_grouped: Cs[i] = Xs[i]^T dYs[i] for every i in one launch (Xs[i] [K, M_i], dYs[i]
+    [K, N_i] bf16, Cs[i] [M_i, N_i] fp32); ws: uint8 device tensor of k_gemm_dw_grouped_ws_bytes."""
+    n = len(Xs)
+    Ms = [x.shape[1] for x in Xs]
+    Ns = [y.shape[1] for y in dYs]
+    _check(lib.als_k_gemm_dw_grouped(n, _ptr_array(Xs), _ptr_array(dYs), _ptr_array(Cs), (C.c_int * n)(*Ms),
+                                     (C.c_int * n)(*Ns), int(K), ws.data_ptr(), ws.numel() * ws.element_size(),
+                                     _stream_handle(stream)))
+
+
 lib.als_k_gemm_ex.argtypes = [_P, _P, _P, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                               _P, _P, _P, _P, C.c_size_t, _P]
 

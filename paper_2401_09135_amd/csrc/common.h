@@ -65,6 +65,41 @@ int gemm_mfma(const GemmDesc& g, hipStream_t st);
 // picks the MFMA kernel when allowed and supported
 int gemm(const GemmDesc& g, bool allow_mfma, hipStream_t st);
 
+// All weight gradients of a backward pass (X^T dY over the batch's tokens, bf16 operands, fp32
+// results) as ONE launch of the 256 x 256 MFMA kernel.  The host turns the list of products into
+// work items: whole rounds of tiles run unsplit over the full contraction and write C directly;
+// the tiles of the last, partial round are split along K so that they fill the chip too, into
+// 256 x 256 partial tiles that a second small kernel adds in slot order.  The records below are what
+// the two kernels read from device memory.
+struct DwProblem {
+  const bf16* A; const bf16* B; float* C;   // A stored [K, M], B stored [K, N], C [M, N]; M, N multiples of 128
+  int M, N, lda, ldb;
+  int pad[2];
+};
+struct DwItem {
+  int prob, tm, tn;
+  int slot;         // -1: whole tile, result straight into C; else index of the partial tile in the workspace
+  int slice0, nk;   // K slices of 64
+  int pad[2];
+};
+struct DwSplitTile { int prob, tm, tn, slot0, nslots, pad[3]; };
+static_assert(sizeof(DwProblem) == 48 && sizeof(DwItem) == 32 && sizeof(DwSplitTile) == 32, "table records");
+struct DwPlan {
+  int n_items, n_split, n_partial_tiles;   // partial tiles are 256 x 256 floats each
+  double flops;
+};
+// Number of CUs the plan fills (MI355X).
+constexpr int DW_PLAN_CUS = 256;
+// Upper bounds of what dw_group_plan writes for n_tiles tiles in all.
+inline int dw_plan_max_items(int n_tiles) { return n_tiles + DW_PLAN_CUS; }
+inline int dw_plan_max_split(int n_tiles) { return n_tiles < DW_PLAN_CUS ? n_tiles : DW_PLAN_CUS; }
+bool dw_group_supported(int M, int N, int K, int64_t lda, int64_t ldb);
+// Shapes only are read from probs (pointers may still be null); items / split receive the tables
+// in launch order (room for dw_plan_max_items / dw_plan_max_split records).
+DwPlan dw_group_plan(const DwProblem* probs, int n_probs, int K, DwItem* items, DwSplitTile* split);
+int dw_group_launch(const DwProblem* d_probs, const DwItem* d_items, const DwSplitTile* d_split, const DwPlan& plan,
+                    float* partial_tiles, hipStream_t st);
+
 // ---- attention ----------------------------------------------------------------------------
 int attention_fwd_generic(const void* qkv, void* o, float* lse, int B, int S, int h, int dh,
                           int bf, hipStream_t st);

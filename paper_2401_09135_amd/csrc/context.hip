@@ -615,6 +615,64 @@ extern "C" int als_k_gemm_static_ws(const void* A, const void* B, void* C, int M
   return gemm_mfma(g, (hipStream_t)stream);
 }
 
+namespace {
+// workspace of the stand-alone grouped weight-gradient call: tables, then partial tiles
+struct DwWsLayout { size_t probs, items, split, partial, total; };
+DwWsLayout dw_ws_layout(int n, int n_tiles) {
+  auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
+  DwWsLayout l;
+  l.probs = 0;
+  l.items = up(l.probs + (size_t)n * sizeof(DwProblem));
+  l.split = up(l.items + (size_t)dw_plan_max_items(n_tiles) * sizeof(DwItem));
+  l.partial = up(l.split + (size_t)dw_plan_max_split(n_tiles) * sizeof(DwSplitTile));
+  l.total = l.partial + (size_t)DW_PLAN_CUS * 65536 * sizeof(float);
+  return l;
+}
+int dw_tiles(int n, const int* M, const int* N) {
+  int t = 0;
+  for (int i = 0; i < n; i++) t += ((M[i] + 255) / 256) * ((N[i] + 255) / 256);
+  return t;
+}
+}  // namespace
+
+extern "C" size_t als_k_gemm_dw_grouped_ws_bytes(int n, const int* M, const int* N) {
+  if (n <= 0 || !M || !N) return 0;
+  for (int i = 0; i < n; i++)
+    if (M[i] <= 0 || N[i] <= 0) return 0;
+  return dw_ws_layout(n, dw_tiles(n, M, N)).total;
+}
+
+extern "C" int als_k_gemm_dw_grouped(int n, const void* const* X, const void* const* dY, float* const* C,
+                                     const int* M, const int* N, int K, void* ws_dev, size_t ws_bytes,
+                                     void* stream) {
+  if (n <= 0 || n > 4096 || !X || !dY || !C || !M || !N || !ws_dev) return set_error(ALS_ERR_INVALID, "null argument or bad count");
+  std::vector<DwProblem> probs(n);
+  for (int i = 0; i < n; i++) {
+    if (!X[i] || !dY[i] || !C[i]) return set_error(ALS_ERR_INVALID, "product %d: null pointer", i);
+    if (M[i] <= 0 || N[i] <= 0 || !dw_group_supported(M[i], N[i], K, M[i], N[i]))
+      return set_error(ALS_ERR_INVALID, "product %d: %d x %d over %d not supported (M, N multiples of 128, K of 64)", i, M[i], N[i], K);
+    if ((uintptr_t)X[i] % 16 || (uintptr_t)dY[i] % 16 || (uintptr_t)C[i] % 16)
+      return set_error(ALS_ERR_INVALID, "product %d: pointers must be 16-byte aligned", i);
+    probs[i] = DwProblem{(const bf16*)X[i], (const bf16*)dY[i], C[i], M[i], N[i], M[i], N[i], {0, 0}};
+  }
+  const int n_tiles = dw_tiles(n, M, N);
+  const DwWsLayout l = dw_ws_layout(n, n_tiles);
+  if ((uintptr_t)ws_dev % 256) return set_error(ALS_ERR_INVALID, "workspace must be 256-byte aligned");
+  if (ws_bytes < l.total) return set_error(ALS_ERR_INVALID, "workspace too small: %zu bytes given, %zu needed", ws_bytes, l.total);
+  std::vector<DwItem> items(dw_plan_max_items(n_tiles));
+  std::vector<DwSplitTile> split(dw_plan_max_split(n_tiles) + 1);
+  const DwPlan plan = dw_group_plan(probs.data(), n, K, items.data(), split.data());
+  char* ws = (char*)ws_dev;
+  hipStream_t st = (hipStream_t)stream;
+  ALS_HIP(hipMemcpyAsync(ws + l.probs, probs.data(), (size_t)n * sizeof(DwProblem), hipMemcpyHostToDevice, st));
+  ALS_HIP(hipMemcpyAsync(ws + l.items, items.data(), (size_t)plan.n_items * sizeof(DwItem), hipMemcpyHostToDevice, st));
+  if (plan.n_split)
+    ALS_HIP(hipMemcpyAsync(ws + l.split, split.data(), (size_t)plan.n_split * sizeof(DwSplitTile), hipMemcpyHostToDevice, st));
+  ALS_HIP(hipStreamSynchronize(st));   // the tables above are host temporaries
+  return dw_group_launch((const DwProblem*)(ws + l.probs), (const DwItem*)(ws + l.items),
+                         (const DwSplitTile*)(ws + l.split), plan, (float*)(ws + l.partial), st);
+}
+
 extern "C" int als_k_gemm_ex(const void* A, const void* B, void* C, int M, int N, int K, int a_layout,
                              int b_layout, int in_dtype, int out_dtype, int use_mfma, int epi, const float* R,
                              void* C2, const void* U, void* ws_dev, size_t ws_bytes, void* stream) {

@@ -506,6 +506,90 @@ int gemm_mfma(const GemmDesc& g, hipStream_t st) {
   return dispatch(g, a, bm, bn, nbuf, 1, st);
 }
 
+bool dw_group_supported(int M, int N, int K, int64_t lda, int64_t ldb) {
+  return M >= 128 && N >= 128 && M % 128 == 0 && N % 128 == 0 && K >= 64 && K % 64 == 0 && lda % 8 == 0 && ldb % 8 == 0;
+}
+
+DwPlan dw_group_plan(const DwProblem* probs, int n_probs, int K, DwItem* items, DwSplitTile* split) {
+  struct T3 { int p, tm, tn; };
+  std::vector<T3> all;
+  DwPlan plan{0, 0, 0, 0.0};
+  for (int p = 0; p < n_probs; p++) {
+    const int tms = (probs[p].M + 255) / 256, tns = (probs[p].N + 255) / 256;
+    // the shorter tile direction fastest: consecutive tiles then share the panels of the longer one
+    if (tms <= tns) { for (int tn = 0; tn < tns; tn++) for (int tm = 0; tm < tms; tm++) all.push_back({p, tm, tn}); }
+    else { for (int tm = 0; tm < tms; tm++) for (int tn = 0; tn < tns; tn++) all.push_back({p, tm, tn}); }
+    plan.flops += 2.0 * probs[p].M * probs[p].N * (double)K;
+  }
+  const int nk_total = K / BK, n_all = (int)all.size();
+  // the last, partial round of tiles is split along K into as many parts as fill the chip (each at
+  // least 4 slices long); a remainder of more than half a round stays whole
+  const int r = n_all % DW_PLAN_CUS;
+  int S = r ? DW_PLAN_CUS / r : 1;
+  if (S > nk_total / 4) S = nk_total / 4;
+  if (S < 1) S = 1;
+  const int n_split = S > 1 ? r : 0, n_whole = n_all - n_split;
+  // whole tiles, in launch order: the workgroups an XCD receives (ids x, x + 8, ...) take a
+  // contiguous run of the list
+  const int base = n_whole / 8, rem = n_whole % 8;
+  for (int id = 0; id < n_whole; id++) {
+    const int x = id & 7, j = id >> 3;
+    const T3& t = all[x * base + (x < rem ? x : rem) + j];
+    items[id] = DwItem{t.p, t.tm, t.tn, -1, 0, nk_total, {0, 0}};
+  }
+  int n = n_whole;
+  if (n_split) {
+    const int q = nk_total / S, rr = nk_total % S;
+    for (int s0 = 0; s0 < S; s0++)
+      for (int i = 0; i < n_split; i++) {
+        const T3& t = all[n_whole + i];
+        items[n++] = DwItem{t.p, t.tm, t.tn, i * S + s0, s0 * q + (s0 < rr ? s0 : rr), q + (s0 < rr ? 1 : 0), {0, 0}};
+      }
+    for (int i = 0; i < n_split; i++) {
+      const T3& t = all[n_whole + i];
+      split[i] = DwSplitTile{t.p, t.tm, t.tn, i * S, S, {0, 0, 0}};
+    }
+  }
+  plan.n_items = n; plan.n_split = n_split; plan.n_partial_tiles = n_split * S;
+  return plan;
+}
+
+int dw_group_launch(const DwProblem* d_probs, const DwItem* d_items, const DwSplitTile* d_split, const DwPlan& plan,
+                    float* partial_tiles, hipStream_t st) {
+  if (plan.n_items <= 0) return ALS_OK;
+  typedef Tile<256, 256, 1, 0, 2> TL;
+  auto kern = gemm_pp_dw_grouped_kernel;
+  static std::atomic<bool> attr_set{false};  // the call is idempotent: a race only repeats it
+  if (!attr_set.load(std::memory_order_acquire)) {
+    ALS_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, TL::LDS_BYTES));
+    attr_set.store(true, std::memory_order_release);
+  }
+  ProfRec rec;
+  bool prof = false;
+  if (g_prof_on) {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (g_prof_on && (g_prof_count++ % (unsigned)g_prof_every) == 0 && hipEventCreate(&rec.e0) == hipSuccess) {
+      if (hipEventCreate(&rec.e1) == hipSuccess) prof = true;
+      else (void)hipEventDestroy(rec.e0);
+    }
+  }
+  if (prof) hipExtLaunchKernelGGL(kern, dim3(plan.n_items), dim3(512), TL::LDS_BYTES, st, rec.e0, rec.e1, 0, d_probs, d_items, partial_tiles);
+  else hipLaunchKernelGGL(kern, dim3(plan.n_items), dim3(512), TL::LDS_BYTES, st, d_probs, d_items, partial_tiles);
+  ALS_CHECK_LAUNCH();
+  if (prof) {
+    rec.id = 1 << 12;   // bit 12: the grouped weight-gradient kernel
+    rec.flops = plan.flops;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    g_prof.push_back(rec);
+  }
+  if (plan.n_split) {
+    hipLaunchKernelGGL(dw_tile_reduce_kernel, dim3(plan.n_split * 16), dim3(256), 0, st, d_probs, d_split, partial_tiles);
+    ALS_CHECK_LAUNCH();
+  }
+  return ALS_OK;
+}
+
 }  // namespace als
 
 // Benchmark hooks: time every MFMA GEMM launch with HIP events on its own stream.
@@ -546,6 +630,7 @@ extern "C" int als_prof_collect(int max_entries, int32_t* ids, int64_t* launches
 extern "C" int als_prof_kernel_name(int id, char* out, int out_len) {
   if (!out || out_len < 1) return als::set_error(ALS_ERR_INVALID, "als_prof_kernel_name: null output");
   static const char* epi[4] = {"STORE", "RESID", "GELU", "DGELU"};
+  if ((id >> 12) & 1) { snprintf(out, out_len, "gemm_pp_dw_grouped_kernel"); return ALS_OK; }
   int nbuf = ((id >> 8) & 3) + 1, bm = ((id & 1) + 1) * 128, bn = (((id >> 1) & 1) + 1) * 128;
   int occ = nbuf == 2 ? (bm == 128 ? 2 : 1) : nbuf == 3 ? 2 : (bm == 256 ? 2 : 3);
   if (nbuf == 4) {

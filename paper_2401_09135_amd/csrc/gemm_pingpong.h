@@ -72,28 +72,19 @@ __device__ __forceinline__ SubTile sub_tile(int wave, int m0, int n0, int M, int
   return by_rows ? SubTile{grp, sub} : SubTile{sub >> 1, grp * 2 + (sub & 1)};
 }
 
-template <int AL, int BL, int EPI, typename TO, bool SPLIT>
-__global__ __launch_bounds__(512, 1) void gemm_pp_kernel(MfmaArgs g) {
+// One 256 x 256 tile: rows m0.., columns n0.., K slices slice0 .. slice0 + nk - 1, results to C
+// (leading dimension g.ldc; the caller has added a split's or a partial tile's offset).
+template <int AL, int BL, int EPI, typename TO>
+__device__ __forceinline__ void pp_tile(const MfmaArgs& g, const int m0, const int n0, const int slice0, const int nk,
+                                        TO* C, char* smem) {
   constexpr int BM = 256, BN = 256;
   typedef Tile<BM, BN, AL, BL, 2> TL;
   static_assert(TL::NT == 512 && TL::A_CHUNKS == 4 && TL::B_CHUNKS == 4, "8 wavefronts, 4 + 4 chunks per thread");
   constexpr int WM = 128, WN = 64, TM = 4, TN = 2;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int grp = wave >> 2;
-
-  const WorkItem wi = work_item<SPLIT>(blockIdx.x, g.tiles_m, g.tiles_n, g.nsplit);
-  const int zsplit = wi.zsplit;
-  const int m0 = wi.tm * BM, n0 = wi.tn * BN;
   const SubTile st = sub_tile(wave, m0, n0, g.M, g.N);
   const int mh = st.mh, ncol0 = st.nq * WN;   // this wavefront's row half and first column inside the tile
-  const int nk_total = g.K / BK;   // split-K: slices dealt to the splits as evenly as whole slices allow
-  int nk = nk_total, slice0 = 0;
-  if (SPLIT) {
-    const int q = nk_total / g.nsplit, r = nk_total % g.nsplit;
-    nk = q + (zsplit < r ? 1 : 0);
-    slice0 = zsplit * q + (zsplit < r ? zsplit : r);
-  }
   const int64_t kbase = (int64_t)slice0 * BK;
 
   // global addressing: scalar tile origin + per-lane, per-chunk 32-bit byte offsets (rows / column
@@ -239,13 +230,92 @@ __global__ __launch_bounds__(512, 1) void gemm_pp_kernel(MfmaArgs g) {
   }
 
   if (!live) return;   // sub-tile outside the matrix
-  TO* C = reinterpret_cast<TO*>(g.C);
-  if (SPLIT) C += (int64_t)zsplit * g.split_stride;
   typedef WaveEpilogue<TM, TN, WN, EPI, TO> EP;
   static_assert(8 * 32 * EP::PITCH <= TL::LDS_BYTES, "epilogue staging must fit the operand buffers");
   EP ep(g, lane, m0 + mh * WM, n0 + ncol0);
   ep.preload();
   ep.run(acc, smem + wave * (32 * EP::PITCH), C);
+}
+
+template <int AL, int BL, int EPI, typename TO, bool SPLIT>
+__global__ __launch_bounds__(512, 1) void gemm_pp_kernel(MfmaArgs g) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const WorkItem wi = work_item<SPLIT>(blockIdx.x, g.tiles_m, g.tiles_n, g.nsplit);
+  const int nk_total = g.K / BK;   // split-K: slices dealt to the splits as evenly as whole slices allow
+  int nk = nk_total, slice0 = 0;
+  TO* C = reinterpret_cast<TO*>(g.C);
+  if (SPLIT) {
+    const int q = nk_total / g.nsplit, r = nk_total % g.nsplit;
+    nk = q + (wi.zsplit < r ? 1 : 0);
+    slice0 = wi.zsplit * q + (wi.zsplit < r ? wi.zsplit : r);
+    C += (int64_t)wi.zsplit * g.split_stride;
+  }
+  pp_tile<AL, BL, EPI, TO>(g, wi.tm * 256, wi.tn * 256, slice0, nk, C, smem);
+}
+
+// ---- all weight gradients of a backward pass in one launch ---------------------------------------
+// Every layer's weight gradient is a product X^T dY over the same contraction length (the tokens of
+// the batch) with few tiles (16-56 for the 150M-class shapes): one product per launch needs a K
+// split of 4-16 to fill the chip, whose fp32 partials cost as much memory traffic as the operands.
+// Here the products of ALL layers are one list of work items built on the host (DwItem: product,
+// tile, K slice range, where the result goes): whole rounds of tiles run unsplit over the full
+// contraction and write the gradient directly; only the tiles of the last, partial round are split
+// along K, so that they fill the chip too, into partial tiles that dw_tile_reduce_kernel adds in
+// slot order.  Items are stored in launch order; the host lays them out so that the workgroups an
+// XCD receives (ids x, x + 8, ...) walk through consecutive tiles of the same products.
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+template <typename T>
+__device__ __forceinline__ T* uniform_ptr(T* p) {
+  const uint64_t u = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u), hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
+  return reinterpret_cast<T*>(((uint64_t)hi << 32) | lo);
+}
+
+__global__ __launch_bounds__(512, 1) void gemm_pp_dw_grouped_kernel(const DwProblem* __restrict__ probs,
+                                                                    const DwItem* __restrict__ items,
+                                                                    float* __restrict__ partial_tiles) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const DwItem it = items[blockIdx.x];
+  const DwProblem pr = probs[uniform(it.prob)];
+  MfmaArgs g;
+  g.A = uniform_ptr(pr.A); g.B = uniform_ptr(pr.B);
+  g.lda = uniform(pr.lda); g.ldb = uniform(pr.ldb);
+  g.M = uniform(pr.M); g.N = uniform(pr.N); g.K = 0;
+  g.tiles_m = 0; g.tiles_n = 0; g.nsplit = 1;
+  g.R = nullptr; g.ldr = 0; g.C2 = nullptr; g.U = nullptr; g.split_stride = 0;
+  const int m0 = uniform(it.tm) * 256, n0 = uniform(it.tn) * 256, slot = uniform(it.slot);
+  float* C;
+  if (slot < 0) {
+    C = uniform_ptr(pr.C);
+    g.ldc = g.N;
+  } else {
+    // a partial tile is stored densely (256 x 256); the epilogue addresses rows and columns of the
+    // whole matrix, so the tile's origin is subtracted from the base
+    C = partial_tiles + (int64_t)slot * 65536 - ((int64_t)m0 * 256 + n0);
+    g.ldc = 256;
+  }
+  g.C = C;
+  pp_tile<1, 0, EPI_STORE, float>(g, m0, n0, uniform(it.slice0), uniform(it.nk), C, smem);
+}
+
+// Adds the partial tiles of the split tiles in slot order and writes the sums into the gradients.
+__global__ __launch_bounds__(256) void dw_tile_reduce_kernel(const DwProblem* __restrict__ probs,
+                                                             const DwSplitTile* __restrict__ tiles,
+                                                             const float* __restrict__ partial_tiles) {
+  const DwSplitTile t = tiles[blockIdx.x >> 4];           // 16 workgroups per tile, 16 rows each
+  const DwProblem pr = probs[t.prob];
+  const int r = (blockIdx.x & 15) * 16 + (threadIdx.x >> 4), c0 = (threadIdx.x & 15) * 4;
+  const int row = t.tm * 256 + r;
+  if (row >= pr.M) return;
+#pragma unroll
+  for (int cc = 0; cc < 4; cc++) {
+    const int c = c0 + cc * 64, col = t.tn * 256 + c;
+    if (col >= pr.N) continue;
+    const float* p = partial_tiles + (int64_t)t.slot0 * 65536 + r * 256 + c;
+    f32x4 a = *reinterpret_cast<const f32x4*>(p);
+    for (int s = 1; s < t.nslots; s++) a += *reinterpret_cast<const f32x4*>(p + (int64_t)s * 65536);
+    *reinterpret_cast<f32x4*>(pr.C + (int64_t)row * pr.N + col) = a;
+  }
 }
 
 // ---- the same ping-pong kernel with operands loaded straight from global memory into LDS ------

@@ -460,3 +460,43 @@ def test_pingpong_forms_agree_bit_for_bit(M, N, K, al, bl):
         out.append(c)
     assert torch.isfinite(out[0]).all()
     assert torch.equal(out[0], out[1])
+
+
+def _grouped_case(shapes, K, seed):
+    rng = np.random.default_rng(seed)
+    Xs = [_dev(rng.standard_normal((K, M)).astype(np.float32), torch.bfloat16) for M, _ in shapes]
+    dYs = [_dev(rng.standard_normal((K, N)).astype(np.float32), torch.bfloat16) for _, N in shapes]
+    Cs = [torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV) for M, N in shapes]
+    ws = torch.empty(A.k_gemm_dw_grouped_ws_bytes([m for m, _ in shapes], [n for _, n in shapes]), dtype=torch.uint8, device=DEV)
+    A.k_gemm_dw_grouped(Xs, dYs, Cs, K, ws)
+    torch.cuda.synchronize()
+    for X, dY, Cm in zip(Xs, dYs, Cs):
+        ref = X.float().cpu().numpy().astype(np.float64).T @ dY.float().cpu().numpy().astype(np.float64)
+        np.testing.assert_allclose(Cm.cpu().numpy(), ref, rtol=1e-4, atol=2e-3 * np.sqrt(K / 64))
+    return Xs, dYs, Cs, ws
+
+
+@pytest.mark.parametrize("shapes,K", [
+    ([(256, 256)], 64),                                              # one tile, one slice: no split possible
+    ([(128, 384), (384, 128), (256, 640)], 1024),                    # 7 tiles, all in the split remainder, half tiles
+    ([(896, 896), (896, 2688), (3584, 896), (896, 3584)] * 2, 512),  # 344 tiles: one whole round and a split remainder
+    ([(512, 2048), (2048, 512), (512, 512), (512, 1536)] * 6, 2048), # 288 tiles, the 20M-class layer set
+    ([(1024, 1024)] * 16, 256),                                      # exactly one round of whole tiles, nothing split
+])
+def test_grouped_weight_gradients(shapes, K):
+    """Every product of the grouped launch against a float64 product of the same bf16 operands:
+    whole tiles, K-split remainder tiles with their reduction, half tiles, and the boundaries of the
+    plan (a single tile, an exact round)."""
+    _grouped_case(shapes, K, seed=[len(shapes), K])
+
+
+def test_grouped_weight_gradients_are_reproducible():
+    """Two launches on the same operands give the same bits (partial tiles are added in slot order)."""
+    shapes = [(896, 2688), (896, 896), (896, 3584), (3584, 896)] * 3
+    Xs, dYs, Cs, ws = _grouped_case(shapes, 1024, seed=7)
+    first = [c.clone() for c in Cs]
+    for c in Cs:
+        c.fill_(float("nan"))
+    A.k_gemm_dw_grouped(Xs, dYs, Cs, 1024, ws)
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(first, Cs))
