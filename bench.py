@@ -32,6 +32,7 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 HEADLINE = "lm150m"
+CONFIG_FLAGS = 0            # als_config.flags of the timed contexts (--config-flags; 2 = one weight-gradient product per matrix)
 # Bytes moved behind the L2s per launch of the dominant GEMM kernel of a workload, measured with
 # rocprofv3 --pmc FETCH_SIZE (x 2.0) and WRITE_SIZE (x 1.0) on the same shapes, one kernel at a time
 # (profiles/gemm_mfma_microbench.md gives the commands, the calibration of the two factors and the
@@ -288,7 +289,7 @@ def run_lm(name, steps_timed, warmup, n_streams, isolated_profile=True):
     k, N = w["k"], w["N"]
     n_events = (warmup + steps_timed) * N
     steps, ev_w, ev_t, ev_g = A.dylu_schedule(w["speeds"], w["H"], w["tau_grace"], n_events)
-    cfg = A.Config.from_workload(w, max_local_steps=int(steps.max()))
+    cfg = A.Config.from_workload(w, flags=CONFIG_FLAGS, max_local_steps=int(steps.max()))
     # parameter layout from the library itself; values N(0, 0.02), gains 1
     P, Pd = A.param_count(cfg), A.param_count_decayed(cfg)
     theta0 = I.theta0([("decayed", (Pd,), "matrix"), ("gains", (P - Pd,), "gain")], w["seed"])
@@ -435,6 +436,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="default run: skip the other workloads")
     ap.add_argument("--streams", type=int, default=0, help="HIP streams the workers share (worker i on stream i mod n); 0 = min(k, 4): the box gives a process 4 hardware queues")
+    ap.add_argument("--config-flags", type=int, default=0, help="tuning: als_config.flags of the timed contexts (bit 1: one weight-gradient product per matrix instead of the grouped launch)")
     ap.add_argument("--gemm-tile", default="", help="tuning: force the MFMA GEMM tile, e.g. 256x128x1 (tile M x tile N x LDS buffers)")
     ap.add_argument("--tiles", default="", help="gemm_microbench: comma-separated tile variants to time next to the automatic choice")
     ap.add_argument("--shapes-of", default="", help="gemm_microbench: the workload whose GEMM shapes are timed")
@@ -450,6 +452,8 @@ def main():
         return gemm_microbench(args)
 
     import paper_2401_09135_amd as A
+    global CONFIG_FLAGS
+    CONFIG_FLAGS = args.config_flags
     if args.gemm_tile:
         A.set_gemm_tile(*[int(x) for x in args.gemm_tile.split("x")])
     name = args.workload or HEADLINE

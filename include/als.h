@@ -69,7 +69,9 @@ typedef struct als_config {
   int32_t n_workers;       /* k, 1..ALS_MAX_WORKERS */
   int32_t dn_N;            /* N >= 1 */
   int32_t max_local_steps; /* capacity of the per-worker loss buffer (>= largest n_steps) */
-  int32_t flags;           /* bit 0: disable the MFMA kernels (use the generic ones) */
+  int32_t flags;           /* bit 0: disable the MFMA kernels (use the generic ones); bit 1: one weight-gradient
+                              product per matrix inside the backward loop instead of the grouped launch of all
+                              layers' weight gradients at its end (bf16 with widths that are multiples of 128) */
   int32_t head_dim;        /* 0 = d/h; otherwise the attention width h*head_dim may differ from d
                               (the paper's 60M / 150M models: 16 heads of 64 on d = 896) */
   int32_t norm_kind;       /* ALS_NORM_RMS (0): y = x rsqrt(mean x^2 + eps) g ; ALS_NORM_LAYER (1): layer

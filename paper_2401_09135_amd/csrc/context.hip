@@ -24,6 +24,14 @@ struct Worker {
   float* losses_dev; float* losses_host;
   int32_t *sort_offset, *sort_rank, *sort_pos;
   float* splitk_ws; size_t splitk_bytes;
+  // Output gradients that the weight-gradient products read (dY), per layer: of the block output
+  // (for W2), of the FFN pre-activation (W1), of the attention block output (Wo), of q/k/v (Wqkv).
+  // With the grouped launch every layer keeps its own until the end of the backward pass; otherwise
+  // all layers point at the same four buffers.
+  std::vector<void*> dy2, dy1, dyo, dyqkv;
+  DwProblem* dw_probs_dev; DwItem* dw_items_dev; DwSplitTile* dw_split_dev; float* dw_partial;
+  std::vector<DwProblem> dw_probs; std::vector<DwItem> dw_items; std::vector<DwSplitTile> dw_split;
+  DwPlan dw_plan;
   int64_t adam_n; int last_n;
   int64_t t_restart;  // server event count when this replica last (re)started
   hipStream_t stream; hipEvent_t done_ev, ready_ev;
@@ -40,6 +48,7 @@ struct als_ctx {
   std::vector<Worker> w;
   hipEvent_t server_ev;
   bool bf; bool allow_mfma;
+  bool grouped_dw;   // the layers' weight gradients run as one grouped launch at the end of the backward pass
   int T;
 };
 
@@ -65,6 +74,8 @@ void carve(als_ctx* c, Carver& cv) {
   int64_t BhS = (int64_t)g.batch * g.n_heads * g.seq_len;
   c->theta = cv.f32(P); c->m = cv.f32(P); c->delta = cv.f32(P);
   c->w.resize(g.n_workers);
+  c->grouped_dw = bf && !(g.flags & 1) && !(g.flags & 2) && g.n_layers > 0 && dw_group_supported((int)d, (int)(3 * da), (int)T, d, 3 * da) &&
+                  dw_group_supported((int)da, (int)d, (int)T, da, d) && dw_group_supported((int)d, (int)ff, (int)T, d, ff);
   for (Worker& w : c->w) {
     w.theta = cv.f32(P); w.start = cv.f32(P); w.adam_m = cv.f32(P); w.adam_v = cv.f32(P);
     w.grad = cv.f32(P);
@@ -97,6 +108,35 @@ void carve(als_ctx* c, Carver& cv) {
       size_t want = (size_t)big * 4 * 16;
       w.splitk_bytes = bf ? (want < ((size_t)64 << 20) ? want : ((size_t)64 << 20)) : 0;
       w.splitk_ws = w.splitk_bytes ? (float*)cv.take(w.splitk_bytes) : nullptr;
+    }
+    w.dy2.assign(L, w.dx_lp); w.dy1.assign(L, w.dff); w.dyo.assign(L, w.dx_lp); w.dyqkv.assign(L, w.dqkv);
+    w.dw_probs_dev = nullptr; w.dw_items_dev = nullptr; w.dw_split_dev = nullptr; w.dw_partial = nullptr;
+    w.dw_plan = DwPlan{0, 0, 0, 0.0};
+    if (c->grouped_dw) {
+      for (int l = 0; l < L; l++) {
+        w.dy2[l] = cv.act(T * d, bf); w.dy1[l] = cv.act(T * ff, bf); w.dyo[l] = cv.act(T * d, bf);
+        w.dyqkv[l] = cv.act(T * 3 * da, bf);
+      }
+      // the products, in the order of the flat parameter layout (pointers are null while only counting)
+      w.dw_probs.clear();
+      int n_tiles = 0;
+      auto add = [&](const void* X, int64_t M, const void* dY, int64_t N, int64_t off) {
+        w.dw_probs.push_back(DwProblem{(const bf16*)X, (const bf16*)dY, w.grad ? w.grad + off : nullptr, (int)M, (int)N, (int)M, (int)N, {0, 0}});
+        n_tiles += (int)(((M + 255) / 256) * ((N + 255) / 256));
+      };
+      for (int l = 0; l < L; l++) {
+        add(w.a[l], d, w.dyqkv[l], 3 * da, c->L.Wqkv[l]);
+        add(w.o[l], da, w.dyo[l], d, c->L.Wo[l]);
+        add(w.b[l], d, w.dy1[l], ff, c->L.W1[l]);
+        add(w.gl[l], ff, w.dy2[l], d, c->L.W2[l]);
+      }
+      w.dw_items.resize(dw_plan_max_items(n_tiles));
+      w.dw_split.resize(dw_plan_max_split(n_tiles) + 1);
+      w.dw_plan = dw_group_plan(w.dw_probs.data(), (int)w.dw_probs.size(), (int)T, w.dw_items.data(), w.dw_split.data());
+      w.dw_probs_dev = (DwProblem*)cv.take(w.dw_probs.size() * sizeof(DwProblem));
+      w.dw_items_dev = (DwItem*)cv.take((size_t)w.dw_plan.n_items * sizeof(DwItem));
+      w.dw_split_dev = (DwSplitTile*)cv.take((size_t)(w.dw_plan.n_split + 1) * sizeof(DwSplitTile));
+      w.dw_partial = cv.f32((int64_t)w.dw_plan.n_partial_tiles * 65536);
     }
   }
 }
@@ -176,30 +216,35 @@ int backward(als_ctx* c, Worker& w, const int32_t* tok, int slot) {
   RUN(gemm(desc(c, w.dlogits, 0, V, wptr(c, w, L.Wout), 1, V, T, d, V, w.dtmp, d, false), mf, st));
   // the norms leave their gain-gradient partials; one kernel adds all of them after the last layer
   const int64_t pset = (int64_t)rmsnorm_bwd_blocks(T) * d;
-  RUN(rmsnorm_bwd(w.dtmp, w.x[nl], w.rstdf, w.theta + L.gf, nullptr, w.dxa, w.dx_lp, c->bf,
+  RUN(rmsnorm_bwd(w.dtmp, w.x[nl], w.rstdf, w.theta + L.gf, nullptr, w.dxa, nl ? w.dy2[nl - 1] : w.dx_lp, c->bf,
                   nullptr, w.partial + 2 * nl * pset, T, d, ln, st));
+  // The weight gradient of every matrix is X^T dY.  Either each is a product of its own, issued
+  // here next to the input gradient that reads the same dY, or (grouped) every layer keeps its four
+  // dY until the loop is over and all of them run as one launch.
+  const bool each = !c->grouped_dw;
   for (int l = nl - 1; l >= 0; l--) {
     // feed-forward block: x_next = xm + gelu(b W1) W2
-    RUN(gemm(desc_dw(c, w, w.gl[l], ff, w.dx_lp, d, ff, d, T, w.grad + L.W2[l]), mf, st));
-    GemmDesc du = desc(c, w.dx_lp, 0, d, wptr(c, w, L.W2[l]), 1, d, T, ff, d, w.dff, ff, true);
+    if (each) RUN(gemm(desc_dw(c, w, w.gl[l], ff, w.dy2[l], d, ff, d, T, w.grad + L.W2[l]), mf, st));
+    GemmDesc du = desc(c, w.dy2[l], 0, d, wptr(c, w, L.W2[l]), 1, d, T, ff, d, w.dy1[l], ff, true);
     du.epi = EPI_DGELU; du.U = w.u[l];
     RUN(gemm(du, mf, st));
-    RUN(gemm(desc_dw(c, w, w.b[l], d, w.dff, ff, d, ff, T, w.grad + L.W1[l]), mf, st));
-    RUN(gemm(desc(c, w.dff, 0, ff, wptr(c, w, L.W1[l]), 1, ff, T, d, ff, w.dtmp, d, false), mf, st));
-    RUN(rmsnorm_bwd(w.dtmp, w.xm[l], w.rstd2[l], w.theta + L.g2[l], w.dxa, w.dxb, w.dx_lp, c->bf,
+    if (each) RUN(gemm(desc_dw(c, w, w.b[l], d, w.dy1[l], ff, d, ff, T, w.grad + L.W1[l]), mf, st));
+    RUN(gemm(desc(c, w.dy1[l], 0, ff, wptr(c, w, L.W1[l]), 1, ff, T, d, ff, w.dtmp, d, false), mf, st));
+    RUN(rmsnorm_bwd(w.dtmp, w.xm[l], w.rstd2[l], w.theta + L.g2[l], w.dxa, w.dxb, w.dyo[l], c->bf,
                     nullptr, w.partial + (2 * l + 1) * pset, T, d, ln, st));
     // attention block: xm = x + attn(a Wqkv) Wo
-    RUN(gemm(desc_dw(c, w, w.o[l], da, w.dx_lp, d, da, d, T, w.grad + L.Wo[l]), mf, st));
-    RUN(gemm(desc(c, w.dx_lp, 0, d, wptr(c, w, L.Wo[l]), 1, d, T, da, d, w.d_o, da, true), mf, st));
+    if (each) RUN(gemm(desc_dw(c, w, w.o[l], da, w.dyo[l], d, da, d, T, w.grad + L.Wo[l]), mf, st));
+    RUN(gemm(desc(c, w.dyo[l], 0, d, wptr(c, w, L.Wo[l]), 1, d, T, da, d, w.d_o, da, true), mf, st));
     if (mf && attention_mfma_supported(S, dh, c->bf))
-      RUN(attention_bwd_mfma(w.qkv[l], w.o[l], w.d_o, w.lse[l], w.Dbuf, w.dqkv, B, S, h, dh, st));
+      RUN(attention_bwd_mfma(w.qkv[l], w.o[l], w.d_o, w.lse[l], w.Dbuf, w.dyqkv[l], B, S, h, dh, st));
     else
-      RUN(attention_bwd_generic(w.qkv[l], w.o[l], w.d_o, w.lse[l], w.Dbuf, w.dqkv, B, S, h, dh, c->bf, st));
-    RUN(gemm(desc_dw(c, w, w.a[l], d, w.dqkv, 3 * da, d, 3 * da, T, w.grad + L.Wqkv[l]), mf, st));
-    RUN(gemm(desc(c, w.dqkv, 0, 3 * da, wptr(c, w, L.Wqkv[l]), 1, 3 * da, T, d, 3 * da, w.dtmp, d, false), mf, st));
-    RUN(rmsnorm_bwd(w.dtmp, w.x[l], w.rstd1[l], w.theta + L.g1[l], w.dxb, w.dxa, w.dx_lp, c->bf,
+      RUN(attention_bwd_generic(w.qkv[l], w.o[l], w.d_o, w.lse[l], w.Dbuf, w.dyqkv[l], B, S, h, dh, c->bf, st));
+    if (each) RUN(gemm(desc_dw(c, w, w.a[l], d, w.dyqkv[l], 3 * da, d, 3 * da, T, w.grad + L.Wqkv[l]), mf, st));
+    RUN(gemm(desc(c, w.dyqkv[l], 0, 3 * da, wptr(c, w, L.Wqkv[l]), 1, 3 * da, T, d, 3 * da, w.dtmp, d, false), mf, st));
+    RUN(rmsnorm_bwd(w.dtmp, w.x[l], w.rstd1[l], w.theta + L.g1[l], w.dxb, w.dxa, l ? w.dy2[l - 1] : w.dx_lp, c->bf,
                     nullptr, w.partial + 2 * l * pset, T, d, ln, st));
   }
+  if (!each) RUN(dw_group_launch(w.dw_probs_dev, w.dw_items_dev, w.dw_split_dev, w.dw_plan, w.dw_partial, st));
   RUN(rmsnorm_dg_sum(w.partial, w.grad + L.g1[0], T, d, 2 * nl + 1, st));
   // w.dtmp (T x d floats) is free again here: scratch for the embedding gradient's chunk partials
   RUN(embed_bwd(tok, w.sort_offset + (int64_t)slot * (V + 1), w.sort_pos + (int64_t)slot * T, w.dxa,
@@ -250,6 +295,16 @@ extern "C" int als_init(const als_config* cfg, void* arena, size_t arena_bytes, 
   c->t = 0;
   Carver cv{(char*)arena, 0};
   carve(c, cv);
+  if (c->grouped_dw)
+    for (Worker& w : c->w) {
+      if (hipMemcpy(w.dw_probs_dev, w.dw_probs.data(), w.dw_probs.size() * sizeof(DwProblem), hipMemcpyHostToDevice) != hipSuccess ||
+          hipMemcpy(w.dw_items_dev, w.dw_items.data(), (size_t)w.dw_plan.n_items * sizeof(DwItem), hipMemcpyHostToDevice) != hipSuccess ||
+          (w.dw_plan.n_split && hipMemcpy(w.dw_split_dev, w.dw_split.data(), (size_t)w.dw_plan.n_split * sizeof(DwSplitTile), hipMemcpyHostToDevice) != hipSuccess)) {
+        int code = set_error(ALS_ERR_HIP, "als_init: uploading the weight-gradient work list failed: %s", hipGetErrorString(hipGetLastError()));
+        delete c;
+        return code;
+      }
+    }
   int64_t P = c->L.P;
   hipStream_t s0 = (hipStream_t)streams[0];
   c->server_ev = nullptr;

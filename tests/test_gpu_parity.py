@@ -80,6 +80,30 @@ def test_loss_and_gradient_one_batch(name, flags):
             off += n
 
 
+@pytest.mark.parametrize("name", ["mini_bf16", "paper60m", "ragged_bf16", "lm20m", "lm150m_b1"])
+def test_grouped_weight_gradients_match_the_per_matrix_products(name):
+    """Config flag bit 1 computes every weight gradient as a product of its own inside the backward
+    loop; the default runs all layers' weight gradients as one grouped launch at its end.  Both read
+    the same bf16 operands and accumulate in fp32, in different orders: every gradient entry agrees to
+    fp32 rounding of its sum, the loss bit for bit (the forward pass is the same code)."""
+    w = I.workload(name)
+    theta0 = I.theta0(lm.param_layout(w), w["seed"])
+    tok = torch.from_numpy(_stream(w)(0).take(1)[0]).to("cuda:0")
+    out = []
+    for flags in (0, 2):
+        ctx = A.Context(A.Config.from_workload(w, flags=flags), theta0, n_streams=1)
+        out.append(ctx.worker_loss_grad(0, tok))
+        ctx.close()
+    (l0, g0), (l1, g1) = out
+    assert l0 == l1
+    off = 0
+    for tname, shape, _ in lm.param_layout(w):
+        n = int(np.prod(shape))
+        a, b = g0[off:off + n], g1[off:off + n]
+        np.testing.assert_allclose(a, b, rtol=2e-4, atol=2e-5 * float(np.abs(b).max()) + 1e-12, err_msg=tname)
+        off += n
+
+
 @pytest.mark.parametrize("name,flags", [("tiny", 0), ("mini_f32", 0), ("mini_bf16", 1), ("mini_bf16", 0),
                                         ("mini_bf16_k16", 0), ("tiny_grace_c", 0), ("mini_bf16_grace_c", 0),
                                         ("wide_attn_f32", 0), ("paper20m", 0), ("paper60m", 0),
