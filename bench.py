@@ -40,10 +40,16 @@ CONFIG_FLAGS = 0            # als_config.flags of the timed contexts (--config-f
 # cannot be collected from inside this process, so the figure is carried here, keyed by workload and
 # kernel, next to the algorithmic bytes of the same launches (operands once + split-K partials
 # written); a kernel without an entry reports null, never another kernel's figure.
-MEASURED_TRAFFIC_BYTES = {"lm20m": {"gemm_pp_kernel<1, 0, STORE, float, true>": 135.5e6},
-                          "lm150m": {"gemm_pp_kernel<1, 0, STORE, float, true>": 211.9e6}}
-ALGORITHMIC_TRAFFIC_BYTES = {"lm20m": {"gemm_pp_kernel<1, 0, STORE, float, true>": 133.9e6},
-                             "lm150m": {"gemm_pp_kernel<1, 0, STORE, float, true>": 168.0e6}}
+MEASURED_TRAFFIC_BYTES = {"lm20m": {"gemm_pp_kernel<0, 1, STORE, float, false>": 127.3e6,
+                                    "gemm_pp_dw_grouped_kernel": 1980.5e6,
+                                    "gemm_pp_kernel<1, 0, STORE, float, true>": 135.5e6},
+                          "lm150m": {"gemm_pp_dw_grouped_kernel": 12872.4e6,
+                                     "gemm_pp_kernel<1, 0, STORE, float, true>": 211.9e6}}
+ALGORITHMIC_TRAFFIC_BYTES = {"lm20m": {"gemm_pp_kernel<0, 1, STORE, float, false>": 110.7e6,
+                                       "gemm_pp_dw_grouped_kernel": 1753.1e6,
+                                       "gemm_pp_kernel<1, 0, STORE, float, true>": 133.9e6},
+                             "lm150m": {"gemm_pp_dw_grouped_kernel": 6166.8e6,
+                                        "gemm_pp_kernel<1, 0, STORE, float, true>": 168.0e6}}
 
 
 def flops_per_token(w):
@@ -264,6 +270,32 @@ def gemm_microbench(args):
                 finally:
                     A.set_gemm_tile(0, 0, 0)
             del a, b, c, R, C2, U
+        # all layers' weight gradients as the backward pass runs them: one grouped launch
+        w = I.workload(wname)
+        T, d, ff = w["B"] * w["S"], w["d"], w["ff"]
+        a_w = w["h"] * w["dh"] if w.get("dh") else d
+        layer = [(d, 3 * a_w), (a_w, d), (d, ff), (ff, d)]
+        if all(m % 128 == 0 and n % 128 == 0 for m, n in layer):
+            Xs = [torch.randn(T, m, device=dev).to(torch.bfloat16) for m, _ in layer * w["L"]]
+            dYs = [torch.randn(T, n, device=dev).to(torch.bfloat16) for _, n in layer * w["L"]]
+            Cs = [torch.empty(m, n, device=dev) for m, n in layer * w["L"]]
+            gws = torch.empty(A.k_gemm_dw_grouped_ws_bytes([m for m, _ in layer * w["L"]], [n for _, n in layer * w["L"]]),
+                              dtype=torch.uint8, device=dev)
+            f = lambda: A.k_gemm_dw_grouped(Xs, dYs, Cs, T, gws)
+            for _ in range(3):
+                f()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(max(args.steps // 4, 3)):
+                f()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / max(args.steps // 4, 3)
+            fl = sum(2.0 * m * n * T for m, n in layer) * w["L"]
+            rows.append(dict(workload=wname, product=f"dw grouped ({4 * w['L']} products)", M=0, N=0, K=T, tile="auto", us=ms * 1e3, tflops=fl / ms / 1e9))
+            print(f"{wname:8s} dw grouped, {4 * w['L']} products, one launch: {ms * 1e3:8.1f} us {rows[-1]['tflops']:6.0f} TFLOP/s", file=sys.stderr, flush=True)
+            del Xs, dYs, Cs, gws
     auto = [r for r in rows if r["tile"] == "auto" and r["product"] != "square 8192"]
     best = max(auto, key=lambda r: r["tflops"])
     print(json.dumps(dict(metric="MFMA GEMM TFLOP/s on the worker step's products", value=best["tflops"], unit="TFLOP/s",
