@@ -728,6 +728,38 @@ extern "C" int als_k_gemm_dw_grouped(int n, const void* const* X, const void* co
                          (const DwSplitTile*)(ws + l.split), plan, (float*)(ws + l.partial), st);
 }
 
+// Host only: the work-item list als_k_gemm_dw_grouped would launch for these shapes, for checking
+// on the CPU that it covers every tile and every K slice exactly once and stays inside its tables.
+extern "C" int als_k_gemm_dw_grouped_plan(int n, const int* M, const int* N, int K, int max_items,
+                                          int32_t* items_out, int max_split, int32_t* split_out,
+                                          int32_t* counts_out) {
+  if (n <= 0 || n > 4096 || !M || !N || !counts_out || (max_items > 0 && !items_out) || (max_split > 0 && !split_out))
+    return set_error(ALS_ERR_INVALID, "null argument or bad count");
+  std::vector<DwProblem> probs(n);
+  for (int i = 0; i < n; i++) {
+    if (M[i] <= 0 || N[i] <= 0 || !dw_group_supported(M[i], N[i], K, M[i], N[i]))
+      return set_error(ALS_ERR_INVALID, "product %d: %d x %d over %d not supported (M, N multiples of 128, K of 64)", i, M[i], N[i], K);
+    probs[i] = DwProblem{nullptr, nullptr, nullptr, M[i], N[i], M[i], N[i], {0, 0}};
+  }
+  const int n_tiles = dw_tiles(n, M, N);
+  std::vector<DwItem> items(dw_plan_max_items(n_tiles));
+  std::vector<DwSplitTile> split(dw_plan_max_split(n_tiles) + 1);
+  const DwPlan plan = dw_group_plan(probs.data(), n, K, items.data(), split.data());
+  counts_out[0] = plan.n_items; counts_out[1] = plan.n_split; counts_out[2] = plan.n_partial_tiles;
+  counts_out[3] = dw_plan_max_items(n_tiles); counts_out[4] = dw_plan_max_split(n_tiles); counts_out[5] = DW_PLAN_CUS;
+  for (int i = 0; i < plan.n_items && i < max_items; i++) {
+    const DwItem& it = items[i];
+    int32_t* o = items_out + 6 * (int64_t)i;
+    o[0] = it.prob; o[1] = it.tm; o[2] = it.tn; o[3] = it.slot; o[4] = it.slice0; o[5] = it.nk;
+  }
+  for (int i = 0; i < plan.n_split && i < max_split; i++) {
+    const DwSplitTile& t = split[i];
+    int32_t* o = split_out + 5 * (int64_t)i;
+    o[0] = t.prob; o[1] = t.tm; o[2] = t.tn; o[3] = t.slot0; o[4] = t.nslots;
+  }
+  return ALS_OK;
+}
+
 extern "C" int als_k_gemm_ex(const void* A, const void* B, void* C, int M, int N, int K, int a_layout,
                              int b_layout, int in_dtype, int out_dtype, int use_mfma, int epi, const float* R,
                              void* C2, const void* U, void* ws_dev, size_t ws_bytes, void* stream) {
