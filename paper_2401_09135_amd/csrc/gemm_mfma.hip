@@ -529,12 +529,21 @@ DwPlan dw_group_plan(const DwProblem* probs, int n_probs, int K, DwItem* items, 
   if (S > nk_total / 4) S = nk_total / 4;
   if (S < 1) S = 1;
   const int n_split = S > 1 ? r : 0, n_whole = n_all - n_split;
-  // whole tiles, in launch order: the workgroups an XCD receives (ids x, x + 8, ...) take a
-  // contiguous run of the list
-  const int base = n_whole / 8, rem = n_whole % 8;
+  // Whole tiles, in launch order.  The chip runs DW_PLAN_CUS tiles at a time, the 32 workgroups an XCD
+  // holds being ids x, x + 8, ...: each such round takes DW_PLAN_CUS consecutive tiles of the list,
+  // XCD x the x-th run of 32 of them.  The tiles of an XCD then share operand panels in its L2, and
+  // the runs of one product sit on neighbouring XCDs at the same time, so that a panel one XCD has
+  // fetched is still in the last-level cache when the next one asks for it (with a contiguous run of
+  // the whole list per XCD instead, every XCD works on layers of its own and each panel comes from
+  // HBM once per XCD round that uses it: 2.5 % slower on the 150M-class shapes).  What is left
+  // behind the last full round is dealt the same way, XCD x taking the x-th of 8 runs of it.
+  const int full = n_whole / DW_PLAN_CUS * DW_PLAN_CUS;
+  const int tail_base = (n_whole - full) / 8, tail_rem = (n_whole - full) % 8;
   for (int id = 0; id < n_whole; id++) {
-    const int x = id & 7, j = id >> 3;
-    const T3& t = all[x * base + (x < rem ? x : rem) + j];
+    const int x = id & 7, j = id >> 3;   // full is a multiple of 8: j counts this XCD's workgroups from 0
+    const int idx = id < full ? (j / 32) * DW_PLAN_CUS + x * 32 + j % 32
+                              : full + x * tail_base + (x < tail_rem ? x : tail_rem) + (j - full / 8);
+    const T3& t = all[idx];
     items[id] = DwItem{t.p, t.tm, t.tn, -1, 0, nk_total, {0, 0}};
   }
   int n = n_whole;

@@ -261,8 +261,9 @@ __global__ __launch_bounds__(512, 1) void gemm_pp_kernel(MfmaArgs g) {
 // tile, K slice range, where the result goes): whole rounds of tiles run unsplit over the full
 // contraction and write the gradient directly; only the tiles of the last, partial round are split
 // along K, so that they fill the chip too, into partial tiles that dw_tile_reduce_kernel adds in
-// slot order.  Items are stored in launch order; the host lays them out so that the workgroups an
-// XCD receives (ids x, x + 8, ...) walk through consecutive tiles of the same products.  The kernel
+// slot order.  Items are stored in launch order; the host lays them out so that the 32 workgroups an
+// XCD holds at a time (ids x, x + 8, ...) are consecutive tiles of the same products and the 8 XCDs
+// hold consecutive runs of the list.  The kernel
 // itself (gemm_pp_dw_grouped_kernel) follows the direct-to-LDS tile body it runs on, further down.
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 template <typename T>
