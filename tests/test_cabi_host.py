@@ -129,7 +129,7 @@ def _lm_dw_shapes(name):
 
 _DW_CASES = [([128], [128], 64), ([256], [256], 256), ([896, 3584, 896, 896], [3584, 896, 896, 2688], 16384),
              ([128] * 7, [384] * 7, 1024), ([256] * 300, [256] * 300, 512), ([1152], [640], 192),
-             ([2048] * 16, [2048] * 16, 128), ([512, 2048, 512, 512] * 6, [2048, 512, 512, 1536] * 6, 16384)]
+             ([2048] * 16, [2048] * 16, 128), ([768] * 50, [768] * 50, 128), ([896, 3584] * 6, [3584, 896] * 6, 256), ([512, 2048, 512, 512] * 6, [2048, 512, 512, 1536] * 6, 16384)]
 
 
 @pytest.mark.parametrize("Ms,Ns,K", _DW_CASES + [(*map(list, zip(*_lm_dw_shapes(n)[0])), _lm_dw_shapes(n)[1])

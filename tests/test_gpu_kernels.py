@@ -482,6 +482,8 @@ def _grouped_case(shapes, K, seed):
     ([(896, 896), (896, 2688), (3584, 896), (896, 3584)] * 2, 512),  # 344 tiles: one whole round and a split remainder
     ([(512, 2048), (2048, 512), (512, 512), (512, 1536)] * 6, 2048), # 288 tiles, the 20M-class layer set
     ([(1024, 1024)] * 16, 256),                                      # exactly one round of whole tiles, nothing split
+    ([(768, 768)] * 50, 128),                                        # 450 tiles, 2 slices each: one round, then 194 unsplit tiles
+    ([(896, 3584), (3584, 896)] * 6, 256),                           # 672 tiles: two rounds and 160 unsplit tiles, half tiles
 ])
 def test_grouped_weight_gradients(shapes, K):
     """Every product of the grouped launch against a float64 product of the same bf16 operands:
