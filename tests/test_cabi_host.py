@@ -24,6 +24,13 @@ def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(A.lib_path)
     for n in names:
         assert hasattr(lib, n), n
+    # the internal measurement / tuning hooks (not part of the ABI) are exported as declared too
+    hooks = open(os.path.join(ROOT, "paper_2401_09135_amd", "csrc", "als_bench.h")).read()
+    hooks = re.sub(r"/\*.*?\*/", "", hooks, flags=re.S)
+    hook_names = sorted(set(re.findall(r"\b(als_[a-z0-9_]+)\s*\(", hooks)))
+    assert "als_k_gemm_dw_grouped_plan" in hook_names
+    for n in hook_names:
+        assert hasattr(lib, n), n
 
 
 @pytest.mark.parametrize("name", list(I.WORKLOADS))
