@@ -16,6 +16,8 @@ microbenchmark (configs[2]) and reports them under config.other_workloads.  Prin
                                                    the MFMA GEMM on the step's shapes, one kernel at a
                                                    time on one stream (the program behind the counter
                                                    runs in profiles/)
+  python bench.py --workload dw_grouped_sweep      the grouped weight-gradient launch on equal products
+                                                   of growing operand footprint
 """
 from __future__ import annotations
 
@@ -307,6 +309,50 @@ def gemm_microbench(args):
                                         kernel=f"{best['workload']} {best['product']}"), cpu_baseline=None)))
 
 
+def dw_grouped_sweep(args):
+    """The grouped weight-gradient launch (als_k_gemm_dw_grouped) on n equal products m x m over
+    K = 16384 tokens, n m^2 fixed: how its rate depends on the operand bytes that have to come from
+    beyond the L2s.  Each size runs with every product on operands of its own, and with the products
+    sharing 1, 2 or 16 operand pairs (pair p mod c), which keeps the L2 behaviour of the distinct case
+    for c >= 2 while the operands fit (or do not fit) the 256 MB last-level cache."""
+    import torch
+    import paper_2401_09135_amd as A
+    dev, T = "cuda:0", 16384
+    rows = []
+    for n, m in ((1024, 256), (256, 512), (64, 1024), (16, 2048), (1, 8192)):
+        for pairs in ([n, 16, 2, 1] if m in (512, 1024) else [n]):
+            X0 = [(torch.randn(T, m, device=dev) * 0.5).to(torch.bfloat16) for _ in range(pairs)]
+            Y0 = [(torch.randn(T, m, device=dev) * 0.5).to(torch.bfloat16) for _ in range(pairs)]
+            Xs, Ys = [X0[p % pairs] for p in range(n)], [Y0[p % pairs] for p in range(n)]
+            Cs = [torch.empty(m, m, device=dev) for _ in range(n)]
+            ws = torch.empty(A.k_gemm_dw_grouped_ws_bytes([m] * n, [m] * n), dtype=torch.uint8, device=dev)
+            best = 1e30
+            for _ in range(3):
+                A.k_gemm_dw_grouped(Xs, Ys, Cs, T, ws)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(args.steps):
+                    A.k_gemm_dw_grouped(Xs, Ys, Cs, T, ws)
+                e1.record()
+                torch.cuda.synchronize()
+                best = min(best, e0.elapsed_time(e1) / args.steps)
+            rows.append(dict(products=n, m=m, operand_pairs=pairs, us=best * 1e3, tflops=2.0 * n * m * m * T / best / 1e9,
+                             unique_operand_TBps=4.0 * pairs * m * T / best / 1e9))
+            print(f"{n:5d} x {m:4d}^2, {pairs:4d} operand pair(s) ({4e-6 * pairs * m * T:7.0f} MB): {best * 1e3:7.0f} us "
+                  f"{rows[-1]['tflops']:6.0f} TFLOP/s, unique operand bytes at {rows[-1]['unique_operand_TBps']:.2f} TB/s",
+                  file=sys.stderr, flush=True)
+            del X0, Y0, Xs, Ys, Cs, ws
+    best = max(rows, key=lambda r: r["tflops"])
+    print(json.dumps(dict(metric="grouped weight-gradient launch, TFLOP/s", value=best["tflops"], unit="TFLOP/s", n_gpus=1,
+                          steps=args.steps, warmup=1, ms_per_step=best["us"] / 1e3, higher_is_better=True, scaling="weak",
+                          vs_baseline=None, dtype="bf16", data="synthetic",
+                          config=dict(workload="dw_grouped_sweep: n products m x m over K = 16384", results=rows),
+                          roofline=dict(bound="mfma", achieved=best["tflops"], peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                                        frac=best["tflops"] / PEAK_BF16_TFLOPS, traffic=None, kernel="gemm_pp_dw_grouped_kernel"),
+                          cpu_baseline=None)))
+
+
 def run_lm(name, steps_timed, warmup, n_streams, isolated_profile=True):
     """Runs warmup + steps_timed outer rounds of one language-model workload and returns the measured
     figures.  Groups of events (ties, grace windows) are applied as the library's schedule marks them
@@ -463,7 +509,7 @@ def main():
     ap.add_argument("--steps", type=int, default=8)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="", help="one workload only (lm150m, lm20m, lm20m_k16, paper150m_b128, "
-                                                   "outer_microbench, gemm_microbench); default: the headline "
+                                                   "outer_microbench, gemm_microbench, dw_grouped_sweep); default: the headline "
                                                    f"workload ({HEADLINE}) followed by short runs of the others")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="default run: skip the other workloads")
@@ -482,6 +528,8 @@ def main():
         return outer_microbench_line(args)
     if args.workload == "gemm_microbench":
         return gemm_microbench(args)
+    if args.workload == "dw_grouped_sweep":
+        return dw_grouped_sweep(args)
 
     import paper_2401_09135_amd as A
     global CONFIG_FLAGS
