@@ -493,6 +493,40 @@ def run_lm(name, steps_timed, warmup, n_streams, isolated_profile=True):
     return res
 
 
+def achieved_ceilings():
+    """What this machine gives plain kernels, so that the fractions of the published peaks can be read:
+    a device-to-device copy of 1 GiB (read + written bytes per second) and the library's own GEMM
+    on an 8192-cube with every operand resident in the last-level cache."""
+    import torch
+    import paper_2401_09135_amd as A
+    dev = "cuda:0"
+    src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+
+    def timed(fn, n):
+        for _ in range(10):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+    ms_copy = timed(lambda: dst.copy_(src), 20)
+    del src, dst
+    n = 8192
+    a = torch.randn(n, n, device=dev).to(torch.bfloat16)
+    b = torch.randn(n, n, device=dev).to(torch.bfloat16)
+    c = torch.empty(n, n, dtype=torch.bfloat16, device=dev)
+    ms_gemm = timed(lambda: A.k_gemm_ex(a, b, c, n, n, n, 0, 1, True, 0, None, None, None, None), 20)
+    return dict(copy_GBps=2.0 * 4 * (1 << 28) / ms_copy / 1e6, copy_frac_of_hbm_peak=2.0 * 4 * (1 << 28) / ms_copy / 1e6 / PEAK_HBM_GBS,
+                gemm_8192_cube_tflops=2.0 * n ** 3 / ms_gemm / 1e9, gemm_8192_cube_frac_of_peak=2.0 * n ** 3 / ms_gemm / 1e9 / PEAK_BF16_TFLOPS,
+                note="device copy of 1 GiB (torch copy_) and als_k_gemm_ex on an 8192-cube (bf16, A row-major, B column-major), 20 launches each after 10 untimed, "
+                     "taken right after the timed workloads, in the power state they leave the chip in")
+
+
 def _brief(r):
     keep = ("describe", "tokens_per_s", "ms_per_outer_round", "outer_rounds_timed", "model_tflops",
             "mfma_frac_whole_path", "outer_step_overhead_fraction", "outer_step_seconds_isolated")
@@ -558,6 +592,8 @@ def main():
         others["outer_microbench"] = {k: dict(GBps=v["GBps"], frac_of_hbm_peak=v["GBps"] / PEAK_HBM_GBS, ms=v["ms"],
                                               bytes_per_param=v["bytes_per_param"]) for k, v in mb.items()}
         out["config"]["other_workloads"] = others
+        if out["roofline"] is not None:
+            out["roofline"]["achieved_ceilings"] = achieved_ceilings()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))
